@@ -1,0 +1,175 @@
+/*
+ * kvfold.h -- C ABI of the KV-Fold fold step for one AMD MI355X (gfx950).
+ *
+ * The fold step is the per-layer attention-with-carried-cache operation of the
+ * paper's Sec. 2 ("KV-Fold"): when chunk t is processed, the queries of its C
+ * new tokens attend to keys K_{0:t} = [K_0; ...; K_t] and values V_{0:t} --
+ * every earlier chunk in full plus a causal mask inside the chunk -- and the
+ * chunk's own K/V rows are appended to the cache that is carried to chunk t+1
+ * (Fig. 2; the recurrence (K^(t),V^(t)) = F((K^(t-1),V^(t-1)), x_t) and its
+ * left-fold form in "A recurrent view").  Position ids continue from tC
+ * (Sec. 2), which this interface expresses as `pos_offset`.
+ *
+ * All entry points are plain C, return an `int` status (0 = KVFOLD_OK,
+ * negative = error), never throw, never print and never abort.  On any error
+ * nothing has been enqueued and the cache state is unchanged.
+ *
+ * Pointer kinds are stated per argument: "host" pointers are ordinary process
+ * memory, "device" pointers are HIP device allocations on the cache's device.
+ */
+#ifndef KVFOLD_H
+#define KVFOLD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kvfold_cache kvfold_cache_t; /* opaque; created/destroyed by the library */
+
+typedef enum { KVFOLD_F32 = 0, KVFOLD_BF16 = 1 } kvfold_dtype_t;
+
+enum {
+  KVFOLD_OK = 0,
+  KVFOLD_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, bad struct_size          */
+  KVFOLD_ERR_BAD_LAYER = -2,   /* layer outside [0, n_layers)                                */
+  KVFOLD_ERR_POSITION = -3,    /* pos_offset != current length of that layer's cache         */
+  KVFOLD_ERR_CAPACITY = -4,    /* length + n_tokens > capacity_tokens (cache untouched)      */
+  KVFOLD_ERR_UNSUPPORTED = -5, /* head_dim not in {64,128}, Hq % Hkv != 0, unknown dtype ... */
+  KVFOLD_ERR_OOM = -6,         /* device allocation failed / caller buffer too small         */
+  KVFOLD_ERR_HIP = -7          /* any other HIP runtime error (see kvfold_last_hip_error)    */
+};
+
+/*
+ * Configuration of a cache.  Shapes follow the paper's models (Tab. 4 caption:
+ * Llama-3.1-8B has 32 layers x 8 KV heads x 128 dims, K and V, 2 bytes in
+ * bf16 = 131,072 bytes per token).  Grouped-query heads: query head h reads KV
+ * head h / (n_q_heads / n_kv_heads).
+ */
+typedef struct {
+  uint32_t struct_size;    /* must be sizeof(kvfold_config_t)                                 */
+  int32_t n_layers;        /* independent per-layer caches, >= 1                              */
+  int32_t n_q_heads;       /* Hq, multiple of n_kv_heads                                      */
+  int32_t n_kv_heads;      /* Hkv >= 1                                                        */
+  int32_t head_dim;        /* d: 64 or 128                                                    */
+  int32_t chunk_tokens;    /* C used by kvfold_step(); also the largest n_tokens of _ex; >= 1 */
+  int64_t capacity_tokens; /* rows reserved per layer; the cache grows in place up to this    */
+  int32_t dtype;           /* kvfold_dtype_t: element type of q, k_new, v_new, cache and out  */
+  float softmax_scale;     /* logits are scaled by this; 0 selects 1/sqrt(head_dim)           */
+  int32_t device;          /* HIP device ordinal the cache lives on                           */
+  void* kv_buffer;         /* device; optional caller-owned storage for the K/V rows, at      */
+                           /* least kvfold_cache_bytes_required() bytes, 256-byte aligned;    */
+                           /* NULL = the library allocates (and frees) it                     */
+  size_t kv_buffer_bytes;  /* size of kv_buffer when it is given                              */
+} kvfold_config_t;
+
+/*
+ * Bytes of K/V storage a cache of this configuration needs:
+ * n_layers * 2 * n_kv_heads * capacity_tokens * head_dim * elem_size (the
+ * paper's per-token figure times capacity; Tab. 4).  Host-only, touches no
+ * GPU.  Returns 0 for an invalid configuration.
+ */
+size_t kvfold_cache_bytes_required(const kvfold_config_t* cfg /* host */);
+
+/*
+ * Create an empty cache (the fold's initial accumulator (empty, empty), Sec. 2).
+ * Layout in HBM: K rows [layer][kv_head][capacity][head_dim], then V rows with
+ * the same shape; a row never moves once written.  Also reserves a fixed
+ * workspace for split-prefix partial results so that steps allocate nothing.
+ * cfg: host.  out_cache: host, receives the handle (NULL on error).
+ */
+int kvfold_cache_create(const kvfold_config_t* cfg, kvfold_cache_t** out_cache);
+
+/*
+ * One fold step on one layer (Sec. 2): append the chunk's C = cfg.chunk_tokens
+ * new K/V rows at rows [pos_offset, pos_offset + C) of the layer's cache, then
+ * compute out[i][h] = softmax_j(scale * q[i][h] . K[h/G][j]) V[h/G][j] over the
+ * keys j <= pos_offset + i.
+ *
+ *   q      device, [C][Hq][d]   queries, used as given (already position-rotated)
+ *   k_new  device, [C][Hkv][d]  new key rows, token-major
+ *   v_new  device, [C][Hkv][d]  new value rows
+ *   pos_offset  absolute position of the chunk's first token; must equal the
+ *               layer's current length (else KVFOLD_ERR_POSITION)
+ *   out    device, [C][Hq][d]   attention output, element type = cfg.dtype
+ *   stream hipStream_t (NULL = default stream)
+ *
+ * Asynchronous: work is enqueued on `stream`, nothing is synchronised or
+ * allocated.  The caller keeps q/k_new/v_new/out alive until the stream has
+ * passed the step.  Steps on the same cache must be issued from one host
+ * thread at a time and be stream-ordered (same stream or explicit events):
+ * the split workspace is shared by all layers of a cache.  The host-side
+ * length of the layer advances by C when the call returns KVFOLD_OK.
+ */
+int kvfold_step(kvfold_cache_t* cache, int layer, const void* q, const void* k_new, const void* v_new,
+                int64_t pos_offset, void* out, void* stream);
+
+/*
+ * Same step with a ragged chunk (1 <= n_tokens <= cfg.chunk_tokens; the paper's
+ * question chunk after the data chunks has its own length, Sec. 4) and an
+ * optional log-sum-exp output:
+ *   lse  device or NULL, [Hq][n_tokens] float: natural-log sum of exp(scaled
+ *        logits) over the visible keys of each row (lets a caller recover the
+ *        softmax weight of any single key).
+ */
+int kvfold_step_ex(kvfold_cache_t* cache, int layer, const void* q, const void* k_new, const void* v_new,
+                   int32_t n_tokens, int64_t pos_offset, void* out, float* lse, void* stream);
+
+/*
+ * Destroy a cache: synchronises the device, frees library-owned memory (never
+ * a caller-provided kv_buffer).  NULL is a no-op returning KVFOLD_OK.
+ */
+int kvfold_cache_destroy(kvfold_cache_t* cache);
+
+/* Current number of rows held for `layer`; negative status on error. Host-only. */
+int64_t kvfold_cache_length(const kvfold_cache_t* cache, int layer);
+
+/*
+ * Device pointers to the first K and V row of `layer` (KV head 0) and the
+ * strides, in elements, between consecutive rows and consecutive KV heads.
+ * Any output pointer may be NULL.  The rows are the complete recurrent state
+ * (Sec. 2, "A recurrent view"): copying rows [0, length) out and back restores
+ * a fold.  Host-only.
+ */
+int kvfold_cache_view(const kvfold_cache_t* cache, int layer, void** k_dev, void** v_dev,
+                      int64_t* row_stride_elems, int64_t* head_stride_elems);
+
+/*
+ * Set the host-side length of `layer` (-1 = every layer) to `new_len`.
+ * new_len <= capacity; rows are left as they are in HBM.  Shrinking rewinds a
+ * fold (re-running a step re-appends identical rows); growing adopts rows a
+ * caller has copied in through kvfold_cache_view (resume).  Host-only; the
+ * caller orders it against in-flight steps.
+ */
+int kvfold_cache_set_length(kvfold_cache_t* cache, int layer, int64_t new_len);
+
+/*
+ * Tuning knobs for measurements (defaults are chosen automatically per step).
+ *   KVFOLD_TUNE_SPLITS         number of prefix splits of the attention kernel; 0 = automatic.
+ *                              Clamped to what the split workspace and the key range allow.
+ *   KVFOLD_TUNE_UNITS_PER_WAVE 32-row query blocks owned by one wavefront of the bf16 kernel:
+ *                              1 or 2; 0 = automatic.
+ * Returns KVFOLD_ERR_INVALID_ARG for an unknown knob or a value out of range.  Host-only.
+ */
+enum { KVFOLD_TUNE_SPLITS = 0, KVFOLD_TUNE_UNITS_PER_WAVE = 1 };
+int kvfold_cache_set_tuning(kvfold_cache_t* cache, int32_t knob, int32_t value);
+
+/*
+ * Launch geometry the next step would use for n_tokens rows at length
+ * `len_after` (for reports): number of workgroups and prefix splits.
+ */
+int kvfold_cache_plan(const kvfold_cache_t* cache, int32_t n_tokens, int64_t len_after, int32_t* n_workgroups,
+                      int32_t* n_splits);
+
+/* Static, human-readable name of a status code. */
+const char* kvfold_status_string(int status);
+
+/* hipError_t value of the last HIP failure seen by this thread's calls (0 = none). */
+int kvfold_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVFOLD_H */

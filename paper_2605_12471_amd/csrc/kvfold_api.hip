@@ -1,0 +1,387 @@
+// Host side of libkvfold: the C ABI declared in include/kvfold.h.
+//
+// One fold step (paper Sec. 2, "KV-Fold" and "A recurrent view") = validate positions, enqueue
+// the append of the chunk's K/V rows, enqueue chunk-prefix attention over rows [0, len + C), and,
+// when the key range was split over workgroups, enqueue the merge.  Everything is stream-ordered;
+// nothing here synchronises or allocates after kvfold_cache_create.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/kvfold.h"
+#include "kvfold_internal.h"
+
+using namespace kvfold;
+
+struct kvfold_cache {
+  kvfold_config_t cfg;
+  int elem_bytes;
+  float scale;
+  unsigned char* kv;  // K block then V block, each [layer][Hkv][cap][d]
+  bool owns_kv;
+  size_t kv_bytes;
+  float* ws_o;   // split workspace: unnormalised partial outputs
+  float* ws_ml;  // split workspace: (max, sum) pairs
+  int64_t ws_rows;
+  int n_cu;
+  std::vector<int64_t> len;
+  int tune_splits;
+  int tune_units_per_wave;
+};
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error = (int)e;
+  (void)hipGetLastError();  // clear the sticky error
+  return e == hipErrorOutOfMemory ? KVFOLD_ERR_OOM : KVFOLD_ERR_HIP;
+}
+
+int elem_size(int dtype) { return dtype == KVFOLD_F32 ? 4 : dtype == KVFOLD_BF16 ? 2 : 0; }
+
+int validate_config(const kvfold_config_t* c) {
+  if (!c || c->struct_size != sizeof(kvfold_config_t)) return KVFOLD_ERR_INVALID_ARG;
+  if (c->n_layers < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->chunk_tokens < 1 || c->capacity_tokens < 1 ||
+      c->device < 0 || !(c->softmax_scale >= 0.f) || !std::isfinite(c->softmax_scale))
+    return KVFOLD_ERR_INVALID_ARG;
+  if (c->kv_buffer && (reinterpret_cast<uintptr_t>(c->kv_buffer) & 255)) return KVFOLD_ERR_INVALID_ARG;
+  if (elem_size(c->dtype) == 0) return KVFOLD_ERR_UNSUPPORTED;
+  if (c->head_dim != 64 && c->head_dim != 128) return KVFOLD_ERR_UNSUPPORTED;
+  if (c->n_q_heads % c->n_kv_heads) return KVFOLD_ERR_UNSUPPORTED;
+  // sizes the kernels index with 32-bit row counts / 64-bit byte offsets
+  if (c->capacity_tokens > (int64_t)1 << 31 || (int64_t)c->chunk_tokens * c->n_q_heads > (int64_t)1 << 28)
+    return KVFOLD_ERR_UNSUPPORTED;
+  if (c->chunk_tokens > c->capacity_tokens) return KVFOLD_ERR_INVALID_ARG;
+  return KVFOLD_OK;
+}
+
+size_t bytes_required(const kvfold_config_t* c) {
+  return (size_t)c->n_layers * 2u * (size_t)c->n_kv_heads * (size_t)c->capacity_tokens * (size_t)c->head_dim *
+         (size_t)elem_size(c->dtype);
+}
+
+constexpr int64_t kMaxSplitRows = 1 << 18;  // cap on S * C * Hq rows held in the split workspace
+constexpr int kMaxSplits = 32;
+constexpr int kMinTilesPerSplit = 8;
+
+struct Plan {
+  int units_per_wave, units_per_head, wgs_per_head, n_splits, tiles_per_split, n_wgs;
+};
+
+Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
+  const kvfold_config_t& f = c->cfg;
+  const int G = f.n_q_heads / f.n_kv_heads;
+  Plan pl;
+  pl.units_per_head = G * ((n_tokens + kRowsPerUnit - 1) / kRowsPerUnit);
+  int upw = 1;
+  if (f.dtype == KVFOLD_BF16) {
+    upw = c->tune_units_per_wave ? c->tune_units_per_wave : 2;
+    // two units per wave only pays when there are enough units to keep every CU busy
+    if (!c->tune_units_per_wave && (int64_t)f.n_kv_heads * pl.units_per_head < (int64_t)c->n_cu * kUnitsPerWg * 2) upw = 1;
+  }
+  pl.units_per_wave = upw;
+  const int per_wg = kUnitsPerWg * upw;
+  pl.wgs_per_head = (pl.units_per_head + per_wg - 1) / per_wg;
+  const int64_t base = (int64_t)f.n_kv_heads * pl.wgs_per_head;
+  const int ntiles = (int)((len_after + kTileKeys - 1) / kTileKeys);
+  int64_t s_max = c->tune_splits > 0 ? ntiles : ntiles / kMinTilesPerSplit;  // a forced count only needs a tile each
+  const int64_t rows = (int64_t)n_tokens * f.n_q_heads;
+  if (c->ws_rows / rows < s_max) s_max = c->ws_rows / rows;
+  if (s_max > kMaxSplits) s_max = kMaxSplits;
+  if (s_max < 1) s_max = 1;
+  int64_t s = 1;
+  if (c->tune_splits > 0) {
+    s = c->tune_splits;
+  } else {
+    const int64_t target = (int64_t)c->n_cu * (upw == 1 ? 2 : 1);  // resident workgroups on the chip
+    if (base * 4 < target * 3) s = (target + base - 1) / base;      // under 3/4 of a wave of workgroups
+  }
+  if (s > s_max) s = s_max;
+  pl.tiles_per_split = (int)((ntiles + s - 1) / s);
+  if (pl.tiles_per_split < 1) pl.tiles_per_split = 1;
+  pl.n_splits = (ntiles + pl.tiles_per_split - 1) / pl.tiles_per_split;
+  if (pl.n_splits < 1) pl.n_splits = 1;
+  pl.n_wgs = (int)(base * pl.n_splits);
+  return pl;
+}
+
+struct DeviceGuard {
+  int prev = -1;
+  bool switched = false;
+  hipError_t err = hipSuccess;
+  explicit DeviceGuard(int dev) {
+    err = hipGetDevice(&prev);
+    if (err == hipSuccess && prev != dev) {
+      err = hipSetDevice(dev);
+      switched = (err == hipSuccess);
+    }
+  }
+  ~DeviceGuard() {
+    if (switched) (void)hipSetDevice(prev);
+  }
+};
+
+}  // namespace
+
+extern "C" {
+
+size_t kvfold_cache_bytes_required(const kvfold_config_t* cfg) {
+  if (validate_config(cfg) != KVFOLD_OK) return 0;
+  return bytes_required(cfg);
+}
+
+int kvfold_cache_create(const kvfold_config_t* cfg, kvfold_cache_t** out_cache) {
+  if (out_cache) *out_cache = nullptr;
+  if (!out_cache) return KVFOLD_ERR_INVALID_ARG;
+  int rc = validate_config(cfg);
+  if (rc != KVFOLD_OK) return rc;
+  const size_t need = bytes_required(cfg);
+  if (cfg->kv_buffer && cfg->kv_buffer_bytes < need) return KVFOLD_ERR_OOM;
+
+  int n_dev = 0;
+  hipError_t e = hipGetDeviceCount(&n_dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (cfg->device >= n_dev) return KVFOLD_ERR_INVALID_ARG;
+  DeviceGuard guard(cfg->device);
+  if (guard.err != hipSuccess) return hip_fail(guard.err);
+
+  kvfold_cache* c = new (std::nothrow) kvfold_cache();
+  if (!c) return KVFOLD_ERR_OOM;
+  c->cfg = *cfg;
+  c->elem_bytes = elem_size(cfg->dtype);
+  c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  c->kv = nullptr;
+  c->owns_kv = false;
+  c->kv_bytes = need;
+  c->ws_o = nullptr;
+  c->ws_ml = nullptr;
+  c->ws_rows = 0;
+  c->tune_splits = 0;
+  c->tune_units_per_wave = 0;
+  c->len.assign((size_t)cfg->n_layers, 0);
+
+  hipDeviceProp_t prop;
+  e = hipGetDeviceProperties(&prop, cfg->device);
+  if (e != hipSuccess) {
+    delete c;
+    return hip_fail(e);
+  }
+  c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+  if (cfg->kv_buffer) {
+    c->kv = static_cast<unsigned char*>(cfg->kv_buffer);
+  } else {
+    void* ptr = nullptr;
+    e = hipMalloc(&ptr, need);
+    if (e != hipSuccess) {
+      delete c;
+      return hip_fail(e);
+    }
+    c->kv = static_cast<unsigned char*>(ptr);
+    c->owns_kv = true;
+  }
+
+  // split workspace: room for kMaxSplits pieces of one chunk, capped
+  const int64_t rows = (int64_t)cfg->chunk_tokens * cfg->n_q_heads;
+  int64_t ws_rows = rows * kMaxSplits;
+  if (ws_rows > kMaxSplitRows) ws_rows = kMaxSplitRows;
+  if (ws_rows < 2 * rows) ws_rows = 0;  // chunks this large never need a split
+  if (ws_rows > 0) {
+    void *po = nullptr, *pm = nullptr;
+    e = hipMalloc(&po, (size_t)ws_rows * cfg->head_dim * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(&pm, (size_t)ws_rows * 2 * sizeof(float));
+    if (e != hipSuccess) {
+      if (po) (void)hipFree(po);
+      if (c->owns_kv) (void)hipFree(c->kv);
+      delete c;
+      return hip_fail(e);
+    }
+    c->ws_o = static_cast<float*>(po);
+    c->ws_ml = static_cast<float*>(pm);
+    c->ws_rows = ws_rows;
+  }
+  *out_cache = c;
+  return KVFOLD_OK;
+}
+
+int kvfold_step_ex(kvfold_cache_t* c, int layer, const void* q, const void* k_new, const void* v_new,
+                   int32_t n_tokens, int64_t pos_offset, void* out, float* lse, void* stream) {
+  if (!c || !q || !k_new || !v_new || !out) return KVFOLD_ERR_INVALID_ARG;
+  const kvfold_config_t& f = c->cfg;
+  if (layer < 0 || layer >= f.n_layers) return KVFOLD_ERR_BAD_LAYER;
+  if (n_tokens < 1 || n_tokens > f.chunk_tokens) return KVFOLD_ERR_INVALID_ARG;
+  const int64_t len_prev = c->len[(size_t)layer];
+  if (pos_offset != len_prev) return KVFOLD_ERR_POSITION;
+  if (len_prev + n_tokens > f.capacity_tokens) return KVFOLD_ERR_CAPACITY;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new) |
+       reinterpret_cast<uintptr_t>(out)) & 15)
+    return KVFOLD_ERR_INVALID_ARG;  // the kernels move 16-byte vectors
+
+  DeviceGuard guard(f.device);
+  if (guard.err != hipSuccess) return hip_fail(guard.err);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  const size_t layer_block = (size_t)f.n_kv_heads * (size_t)f.capacity_tokens * (size_t)f.head_dim * c->elem_bytes;
+  unsigned char* k_layer = c->kv + (size_t)layer * layer_block;
+  unsigned char* v_layer = c->kv + c->kv_bytes / 2 + (size_t)layer * layer_block;
+
+  AppendParams ap;
+  ap.k_new = k_new;
+  ap.v_new = v_new;
+  ap.k_cache = k_layer;
+  ap.v_cache = v_layer;
+  ap.n_tokens = n_tokens;
+  ap.n_kv_heads = f.n_kv_heads;
+  ap.row_bytes = f.head_dim * c->elem_bytes;
+  ap.capacity = f.capacity_tokens;
+  ap.len_prev = len_prev;
+
+  const Plan pl = make_plan(c, n_tokens, len_prev + n_tokens);
+  AttnParams at;
+  at.q = q;
+  at.k_cache = k_layer;
+  at.v_cache = v_layer;
+  at.out = out;
+  at.lse = lse;
+  at.part_o = c->ws_o;
+  at.part_ml = c->ws_ml;
+  at.n_tokens = n_tokens;
+  at.n_q_heads = f.n_q_heads;
+  at.n_kv_heads = f.n_kv_heads;
+  at.group = f.n_q_heads / f.n_kv_heads;
+  at.capacity = f.capacity_tokens;
+  at.len_prev = len_prev;
+  at.n_splits = pl.n_splits;
+  at.tiles_per_split = pl.tiles_per_split;
+  at.units_per_head = pl.units_per_head;
+  at.wgs_per_head = pl.wgs_per_head;
+  at.n_wgs = pl.n_wgs;
+  at.scale_log2e = c->scale * 1.4426950408889634f;
+  if (pl.n_splits > 1 && (int64_t)pl.n_splits * n_tokens * f.n_q_heads > c->ws_rows) return KVFOLD_ERR_HIP;  // planner bug guard
+
+  hipError_t e = launch_append(ap, s);
+  if (e != hipSuccess) return hip_fail(e);
+  e = (f.dtype == KVFOLD_BF16) ? launch_attn_bf16(at, f.head_dim, pl.units_per_wave, s) : launch_attn_f32(at, f.head_dim, s);
+  if (e != hipSuccess) return hip_fail(e);
+  if (pl.n_splits > 1) {
+    CombineParams cp;
+    cp.part_o = c->ws_o;
+    cp.part_ml = c->ws_ml;
+    cp.out = out;
+    cp.lse = lse;
+    cp.n_rows = n_tokens * f.n_q_heads;
+    cp.n_tokens = n_tokens;
+    cp.n_q_heads = f.n_q_heads;
+    cp.head_dim = f.head_dim;
+    cp.n_splits = pl.n_splits;
+    cp.out_is_bf16 = f.dtype == KVFOLD_BF16;
+    e = launch_combine(cp, s);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  c->len[(size_t)layer] = len_prev + n_tokens;
+  return KVFOLD_OK;
+}
+
+int kvfold_step(kvfold_cache_t* c, int layer, const void* q, const void* k_new, const void* v_new, int64_t pos_offset,
+                void* out, void* stream) {
+  if (!c) return KVFOLD_ERR_INVALID_ARG;
+  return kvfold_step_ex(c, layer, q, k_new, v_new, c->cfg.chunk_tokens, pos_offset, out, nullptr, stream);
+}
+
+int kvfold_cache_destroy(kvfold_cache_t* c) {
+  if (!c) return KVFOLD_OK;
+  int rc = KVFOLD_OK;
+  {
+    DeviceGuard guard(c->cfg.device);
+    if (guard.err != hipSuccess) rc = hip_fail(guard.err);
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) rc = hip_fail(e);
+    if (c->owns_kv && c->kv) (void)hipFree(c->kv);
+    if (c->ws_o) (void)hipFree(c->ws_o);
+    if (c->ws_ml) (void)hipFree(c->ws_ml);
+  }
+  delete c;
+  return rc;
+}
+
+int64_t kvfold_cache_length(const kvfold_cache_t* c, int layer) {
+  if (!c) return KVFOLD_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= c->cfg.n_layers) return KVFOLD_ERR_BAD_LAYER;
+  return c->len[(size_t)layer];
+}
+
+int kvfold_cache_view(const kvfold_cache_t* c, int layer, void** k_dev, void** v_dev, int64_t* row_stride_elems,
+                      int64_t* head_stride_elems) {
+  if (!c) return KVFOLD_ERR_INVALID_ARG;
+  const kvfold_config_t& f = c->cfg;
+  if (layer < 0 || layer >= f.n_layers) return KVFOLD_ERR_BAD_LAYER;
+  const size_t layer_block = (size_t)f.n_kv_heads * (size_t)f.capacity_tokens * (size_t)f.head_dim * c->elem_bytes;
+  if (k_dev) *k_dev = c->kv + (size_t)layer * layer_block;
+  if (v_dev) *v_dev = c->kv + c->kv_bytes / 2 + (size_t)layer * layer_block;
+  if (row_stride_elems) *row_stride_elems = f.head_dim;
+  if (head_stride_elems) *head_stride_elems = f.capacity_tokens * f.head_dim;
+  return KVFOLD_OK;
+}
+
+int kvfold_cache_set_length(kvfold_cache_t* c, int layer, int64_t new_len) {
+  if (!c) return KVFOLD_ERR_INVALID_ARG;
+  if (layer < -1 || layer >= c->cfg.n_layers) return KVFOLD_ERR_BAD_LAYER;
+  if (new_len < 0) return KVFOLD_ERR_INVALID_ARG;
+  if (new_len > c->cfg.capacity_tokens) return KVFOLD_ERR_CAPACITY;
+  if (layer == -1)
+    for (auto& v : c->len) v = new_len;
+  else
+    c->len[(size_t)layer] = new_len;
+  return KVFOLD_OK;
+}
+
+int kvfold_cache_set_tuning(kvfold_cache_t* c, int32_t knob, int32_t value) {
+  if (!c) return KVFOLD_ERR_INVALID_ARG;
+  switch (knob) {
+    case KVFOLD_TUNE_SPLITS:
+      if (value < 0 || value > kMaxSplits) return KVFOLD_ERR_INVALID_ARG;
+      c->tune_splits = value;
+      return KVFOLD_OK;
+    case KVFOLD_TUNE_UNITS_PER_WAVE:
+      if (value < 0 || value > 2) return KVFOLD_ERR_INVALID_ARG;
+      c->tune_units_per_wave = value;
+      return KVFOLD_OK;
+    default:
+      return KVFOLD_ERR_INVALID_ARG;
+  }
+}
+
+int kvfold_cache_plan(const kvfold_cache_t* c, int32_t n_tokens, int64_t len_after, int32_t* n_workgroups,
+                      int32_t* n_splits) {
+  if (!c || n_tokens < 1 || n_tokens > c->cfg.chunk_tokens || len_after < n_tokens ||
+      len_after > c->cfg.capacity_tokens)
+    return KVFOLD_ERR_INVALID_ARG;
+  const Plan pl = make_plan(c, n_tokens, len_after);
+  if (n_workgroups) *n_workgroups = pl.n_wgs;
+  if (n_splits) *n_splits = pl.n_splits;
+  return KVFOLD_OK;
+}
+
+const char* kvfold_status_string(int status) {
+  switch (status) {
+    case KVFOLD_OK: return "ok";
+    case KVFOLD_ERR_INVALID_ARG: return "invalid argument";
+    case KVFOLD_ERR_BAD_LAYER: return "layer out of range";
+    case KVFOLD_ERR_POSITION: return "pos_offset does not continue the cache";
+    case KVFOLD_ERR_CAPACITY: return "cache capacity exceeded";
+    case KVFOLD_ERR_UNSUPPORTED: return "unsupported configuration";
+    case KVFOLD_ERR_OOM: return "out of device memory or buffer too small";
+    case KVFOLD_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int kvfold_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+// Internal declarations shared by the HIP translation units of libkvfold (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kvfold {
+
+// Rows of one (query head, 32-token block) pair are the unit of work of one wavefront.
+constexpr int kRowsPerUnit = 32;
+// Wavefronts (units) per workgroup of the attention kernels.
+constexpr int kUnitsPerWg = 4;
+// Keys per K/V tile staged through LDS.
+constexpr int kTileKeys = 64;
+
+struct AppendParams {
+  const void* k_new;  // [C][Hkv][d]
+  const void* v_new;  // [C][Hkv][d]
+  void* k_cache;      // layer base, [Hkv][cap][d]
+  void* v_cache;
+  int32_t n_tokens;   // C
+  int32_t n_kv_heads;
+  int32_t row_bytes;  // d * elem_size, multiple of 16
+  int64_t capacity;   // rows per head
+  int64_t len_prev;   // first destination row
+};
+
+struct AttnParams {
+  const void* q;         // [C][Hq][d]
+  const void* k_cache;   // layer base, [Hkv][cap][d]; rows [0, len_prev + C) valid
+  const void* v_cache;
+  void* out;             // [C][Hq][d]
+  float* lse;            // [Hq][C] or nullptr
+  float* part_o;         // [S][C*Hq][d]  unnormalised partial outputs (split mode)
+  float* part_ml;        // [S][C*Hq][2]  (running max in log2 units, partial sum)
+  int32_t n_tokens;      // C
+  int32_t n_q_heads;     // Hq
+  int32_t n_kv_heads;    // Hkv
+  int32_t group;         // G = Hq / Hkv
+  int64_t capacity;      // rows per head in the cache
+  int64_t len_prev;      // cache length before this chunk
+  int32_t n_splits;      // S >= 1; S == 1 writes out/lse directly
+  int32_t tiles_per_split;
+  int32_t units_per_head;  // G * ceil(C / 32)
+  int32_t wgs_per_head;    // ceil(units_per_head / units per workgroup)
+  int32_t n_wgs;           // Hkv * wgs_per_head * S (the grid is padded to a multiple of 8)
+  float scale_log2e;       // softmax scale * log2(e)
+};
+
+struct CombineParams {
+  const float* part_o;
+  const float* part_ml;
+  void* out;
+  float* lse;          // [Hq][C] or nullptr
+  int32_t n_rows;      // C * Hq
+  int32_t n_tokens;    // C
+  int32_t n_q_heads;
+  int32_t head_dim;
+  int32_t n_splits;
+  int32_t out_is_bf16;
+};
+
+hipError_t launch_append(const AppendParams& p, hipStream_t s);
+hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, int units_per_wave, hipStream_t s);
+hipError_t launch_attn_f32(const AttnParams& p, int head_dim, hipStream_t s);
+hipError_t launch_combine(const CombineParams& p, hipStream_t s);
+
+// Padded grid size and the XCD-aware remap used by the attention kernels: the hardware hands
+// workgroup b to XCD b % 8, so logical ids are dealt out in 8 contiguous ranges, one per XCD,
+// which keeps the workgroups of one KV head on one XCD's L2.
+constexpr int kNumXcd = 8;
+inline int padded_grid(int n_wgs) { return (n_wgs + kNumXcd - 1) / kNumXcd * kNumXcd; }
+
+}  // namespace kvfold

@@ -1,0 +1,113 @@
+"""GPU parity of the HIP fold step against the fp64 oracle, element by element, on sizes the oracle
+finishes in seconds but that span several tiles, ragged tails, splits and both wave shapes."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_12471_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import fold_harness
+    return fold_harness
+
+
+def _run_case(H, oracle, cfg, chunks, splits=0, upw=0, check_lse=True):
+    gpu = H.GpuFold(cfg, capacity=sum(chunks), chunk_tokens=max(chunks))
+    oc = H.make_oracle(oracle, cfg, capacity=sum(chunks))
+    if splits:
+        gpu.cache.set_tuning(0, splits)
+    if upw:
+        gpu.cache.set_tuning(1, upw)
+    pos, worst = 0, 0.0
+    try:
+        for step, C in enumerate(chunks):
+            q, k, v = I.chunk_qkv(cfg, 0, step, n_tokens=C, token_base=pos)
+            out, lse = gpu.step(0, q, k, v, want_lse=True)
+            ref, ref_lse = H.oracle_step(oc, q, k, v)
+            torch.cuda.synchronize()
+            err = np.abs(H.wide(out) - ref).max()
+            worst = max(worst, err)
+            assert err <= H.TOL[cfg.dtype], f"step {step} C={C} pos={pos}: max|out-oracle|={err}"
+            if check_lse:
+                lerr = np.abs(lse.cpu().double().numpy().T - ref_lse).max()
+                assert lerr <= (1e-5 if cfg.dtype == "f32" else 2e-2), f"step {step}: lse err {lerr}"
+            pos += C
+        H.assert_cache_bit_exact(gpu, oc)
+    finally:
+        gpu.close()
+    return worst
+
+
+def test_config1_tiny_fp32_vs_oracle_and_monolithic(H, oracle):
+    """Benchmark config 1: 1 layer, Hq=4, Hkv=1, d=64, C=128, 4 chunks, fp32, tolerance 1e-5."""
+    cfg = I.CONFIGS["tiny_f32"]
+    gpu = H.GpuFold(cfg)
+    oc = H.make_oracle(oracle, cfg)
+    outs, Q, K, V = [], [], [], []
+    try:
+        for step in range(cfg.n_steps):
+            q, k, v = I.chunk_qkv(cfg, 0, step)
+            out = gpu.step(0, q, k, v)
+            ref, _ = H.oracle_step(oc, q, k, v)
+            assert np.abs(H.wide(out) - ref).max() <= 1e-5
+            outs.append(H.wide(out)); Q.append(H.wide(q)); K.append(H.wide(k)); V.append(H.wide(v))
+        H.assert_cache_bit_exact(gpu, oc)
+    finally:
+        gpu.close()
+    mono, _ = oracle.monolithic_causal_attention(np.concatenate(Q), np.concatenate(K), np.concatenate(V))
+    assert np.abs(np.concatenate(outs) - mono).max() <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("Hq,Hkv,d", [(4, 1, 64), (8, 2, 128), (7, 1, 128), (6, 3, 64)])
+def test_ragged_chunks(H, oracle, dtype, Hq, Hkv, d):
+    cfg = I.FoldConfig("ragged", 10, 1, Hq, Hkv, d, 100, 0, dtype)
+    _run_case(H, oracle, cfg, [100, 1, 33, 64, 7, 95])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("splits", [2, 3, 5])
+def test_forced_splits(H, oracle, dtype, splits):
+    cfg = I.FoldConfig("splits", 11, 1, 8, 2, 128, 64, 0, dtype)
+    _run_case(H, oracle, cfg, [64] * 3 + [40] + [64] * 20, splits=splits)
+
+
+@pytest.mark.parametrize("upw", [1, 2])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (28, 4), (4, 4)])
+def test_units_per_wave_bf16(H, oracle, upw, Hq, Hkv):
+    cfg = I.FoldConfig("upw", 12, 1, Hq, Hkv, 128, 160, 0, "bf16")
+    _run_case(H, oracle, cfg, [160, 160, 50, 160], upw=upw)
+
+
+def test_isolated_chunk_equals_plain_causal(H, oracle):
+    """Empty cache (the paper's ISOLATED condition, Sec. 2): the step is plain causal attention."""
+    cfg = I.FoldConfig("iso", 13, 1, 8, 4, 128, 256, 0, "bf16")
+    q, k, v = I.chunk_qkv(cfg, 0, 0)
+    gpu = H.GpuFold(cfg, capacity=256)
+    try:
+        out = gpu.step(0, q, k, v)
+        mono, _ = oracle.monolithic_causal_attention(H.wide(q), H.wide(k), H.wide(v))
+        assert np.abs(H.wide(out) - mono).max() <= 2e-2
+    finally:
+        gpu.close()
+
+
+def test_layers_are_independent(H, oracle):
+    cfg = I.FoldConfig("layers", 14, 3, 8, 2, 128, 64, 0, "bf16")
+    gpu = H.GpuFold(cfg, capacity=192)
+    ocs = [H.make_oracle(oracle, cfg, capacity=192) for _ in range(3)]
+    try:
+        for step in range(3):
+            for layer in (2, 0, 1):
+                q, k, v = I.chunk_qkv(cfg, layer, step)
+                out = gpu.step(layer, q, k, v)
+                ref, _ = H.oracle_step(ocs[layer], q, k, v)
+                assert np.abs(H.wide(out) - ref).max() <= 2e-2
+        for layer in range(3):
+            H.assert_cache_bit_exact(gpu, ocs[layer], layer)
+    finally:
+        gpu.close()
