@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV-Fold fold step on one MI355X.
+
+A bench "step" is one complete fold of the headline workload: the Llama-3.1-8B-shaped layer of the
+benchmark definition (Hq=32, Hkv=8, d=128, bf16, C=2048, 8 chunks = 16K tokens), i.e. 8 calls of
+kvfold_step (append + chunk-prefix attention [+ merge]) starting from an empty cache.  All inputs
+are resident in HBM before the timed region.  The headline value is useful attention TFLOP/s
+(4*Hq*d*C*(L_prev + (C+1)/2) per fold step, masked pairs not counted) of the whole fold.
+
+One JSON line is printed with the driver's fields plus
+  roofline      dominant kernel (chunk-prefix attention) against the bf16 dense MFMA peak, its
+                duration measured with HIP events recorded by the library on the step's stream
+  cpu_baseline  the fp64 oracle timed on this machine's host cores on a bounded sample of the same
+                workload (also used as a spot check of the GPU output)
+  extra         tokens/s and TFLOP/s against cache length for this and the long-context shapes
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA (256 CU x 4096 FLOP/clk x 2.4 GHz)
+PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def step_flops(cfg, C, L_prev):
+    """Useful FLOPs of one fold step: QK^T and PV over the unmasked (row, key) pairs."""
+    return 4.0 * cfg.n_q_heads * cfg.head_dim * C * (L_prev + (C + 1) / 2.0)
+
+
+def step_bytes(cfg, C, L_prev):
+    """Algorithmic HBM bytes of one fold step: cache read once, q read, out written, append read+write."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    L = L_prev + C
+    return (2 * cfg.n_kv_heads * cfg.head_dim * L * es + 2 * C * cfg.n_q_heads * cfg.head_dim * es
+            + 4 * C * cfg.n_kv_heads * cfg.head_dim * es)
+
+
+class Workload:
+    """All chunks of one layer resident on the GPU + a library cache."""
+
+    def __init__(self, cfg, torch, kv, I, device, n_steps=None, tuning=None):
+        self.cfg, self.torch = cfg, torch
+        self.n_steps = n_steps or cfg.n_steps
+        self.cache = kv.KvFoldCache(1, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.chunk,
+                                    self.n_steps * cfg.chunk, cfg.dtype, device=device.index or 0)
+        for knob, val in (tuning or {}).items():
+            self.cache.set_tuning(knob, val)
+        self.chunks = [I.chunk_qkv(cfg, 0, s, device=device) for s in range(self.n_steps)]
+        self.out = torch.empty_like(self.chunks[0][0])
+        self.flops = sum(step_flops(cfg, cfg.chunk, s * cfg.chunk) for s in range(self.n_steps))
+        self.bytes = sum(step_bytes(cfg, cfg.chunk, s * cfg.chunk) for s in range(self.n_steps))
+
+    def fold(self):
+        self.cache.set_length(0, 0)
+        for s, (q, k, v) in enumerate(self.chunks):
+            self.cache.step(0, q, k, v, self.out, pos_offset=s * self.cfg.chunk)
+
+    def per_step_curve(self, reps=3):
+        """Event-timed single steps against a cache rewound to each length: [(L_prev, ms)]."""
+        torch = self.torch
+        self.fold()
+        torch.cuda.synchronize()
+        res = []
+        for s, (q, k, v) in enumerate(self.chunks):
+            best = None
+            for _ in range(reps):
+                self.cache.set_length(0, s * self.cfg.chunk)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                self.cache.step(0, q, k, v, self.out, pos_offset=s * self.cfg.chunk)
+                e1.record()
+                e1.synchronize()
+                ms = e0.elapsed_time(e1)
+                best = ms if best is None else min(best, ms)
+            res.append((s * self.cfg.chunk, best))
+        return res
+
+    def close(self):
+        self.cache.close()
+
+
+def time_folds(w, torch, steps, warmup):
+    for _ in range(warmup):
+        w.fold()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        w.fold()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def profiled_folds(w, steps):
+    """Same folds with the library's per-kernel HIP events: returns summed kernel milliseconds."""
+    w.cache.profile_begin(steps * w.n_steps)
+    for _ in range(steps):
+        w.fold()
+    n, append_ms, attn_ms, merge_ms = w.cache.profile_end()
+    return n, append_ms, attn_ms, merge_ms
+
+
+def cpu_baseline(w, torch, n_rows=512):
+    """Time the fp64 oracle on a seeded sample of rows of the LAST fold step of the workload and
+    compare the GPU output on those rows."""
+    import numpy as np
+    from oracle import kvfold_oracle as O
+    from paper_2605_12471_amd import inputs as I
+    cfg = w.cfg
+    O.build()
+    store = np.uint16 if cfg.dtype == "bf16" else np.float32
+
+    def bits(t):
+        t = t.cpu().contiguous()
+        return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+    oc = O.OracleCache(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, w.n_steps * cfg.chunk, store_dtype=store)
+    for q, k, v in w.chunks[:-1]:
+        oc.append(bits(k), bits(v))
+    q, k, v = w.chunks[-1]
+    last = w.n_steps - 1
+    rows = I.sample_rows(cfg, last, n_random=n_rows)
+    L_prev = oc.len
+    t0 = time.perf_counter()
+    ref, _ = oc.step(q.cpu().double().numpy(), bits(k), bits(v), L_prev, rows=rows)
+    dt = time.perf_counter() - t0
+    flops = sum(4.0 * cfg.head_dim * (L_prev + r + 1) for r in rows) * cfg.n_q_heads
+    # GPU output of the same step
+    w.fold()
+    torch.cuda.synchronize()
+    got = w.out.cpu().double().numpy()[rows]
+    err = float(np.abs(got - ref).max())
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": O.threads(), "kind": "oracle",
+        "sample": f"last fold step (L_prev={L_prev}, C={cfg.chunk}): {len(rows)} seeded rows x {cfg.n_q_heads} heads, "
+                  f"{flops / 1e9:.1f} GFLOP fp64 in {dt:.1f} s",
+        "tokens_per_s_at_L": len(rows) / dt, "gpu_max_abs_err_on_sample": err,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama_16k")
+    ap.add_argument("--no-extra", action="store_true", help="skip the long-context curves")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--units-per-wave", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2605_12471_amd as kv
+    from paper_2605_12471_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    kv.load_library()  # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = I.CONFIGS[args.workload]
+    tuning = {}
+    if args.splits:
+        tuning[kv.TUNE_SPLITS] = args.splits
+    if args.units_per_wave:
+        tuning[kv.TUNE_UNITS_PER_WAVE] = args.units_per_wave
+
+    w = Workload(cfg, torch, kv, I, dev, tuning=tuning)
+    ms = time_folds(w, torch, args.steps, args.warmup)
+    tflops = w.flops / (ms * 1e-3) / 1e12
+    tokens_per_s = cfg.total_tokens / (ms * 1e-3)
+
+    n_prof, append_ms, attn_ms, merge_ms = profiled_folds(w, args.steps)
+    attn_avg_ms = attn_ms / max(n_prof, 1)
+    attn_tflops = (w.flops * args.steps) / (attn_ms * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
+    roofline = {
+        "kernel": "attn_bf16_kernel" if cfg.dtype == "bf16" else "attn_f32_kernel",
+        "bound": "mfma", "achieved": attn_tflops, "peak": peak, "unit": "TFLOP/s", "frac": attn_tflops / peak,
+        "traffic": None,
+        "launches": n_prof, "avg_launch_ms": attn_avg_ms, "flops_per_launch_avg": w.flops / w.n_steps,
+        "algorithmic_bytes_per_launch_avg": w.bytes / w.n_steps,
+        "achieved_hbm_GBps_algorithmic": w.bytes * args.steps / (attn_ms * 1e-3) / 1e9,
+        "append_ms_avg": append_ms / max(n_prof, 1), "merge_ms_avg": merge_ms / max(n_prof, 1),
+    }
+
+    extra = {}
+    curve = w.per_step_curve()
+    extra["curve_" + cfg.name] = [
+        {"L_prev": L, "ms": t, "tflops": step_flops(cfg, cfg.chunk, L) / (t * 1e-3) / 1e12,
+         "tokens_per_s": cfg.chunk / (t * 1e-3)} for L, t in curve]
+
+    result = {
+        "metric": "chunk-prefix attention TFLOP/s (useful FLOPs of a whole fold / wall time)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: 1 layer, Hq={cfg.n_q_heads}, Hkv={cfg.n_kv_heads}, d={cfg.head_dim}, "
+                               f"C={cfg.chunk}, fold to {cfg.total_tokens} tokens ({cfg.n_steps} steps)",
+                   "seed": I.BASE_SEED, "step": "one whole fold from an empty cache"},
+        "frac_of_bf16_peak": tflops / PEAK_BF16_TFLOPS, "fold_tokens_per_s": tokens_per_s,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, torch)
+    w.close()
+
+    if not args.no_extra:
+        # long-context operating points of the benchmark definition (single layer each)
+        for name, n_steps in (("full_stack_128k", None), ("deep_chain_128k", None)):
+            c2 = I.CONFIGS[name].with_(n_layers=1)
+            w2 = Workload(c2, torch, kv, I, dev, tuning=tuning)
+            w2.fold()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            w2.fold()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            n, a_ms, t_ms, m_ms = profiled_folds(w2, 1)
+            pts = w2.per_step_curve(reps=2)
+            sel = pts if len(pts) <= 32 else pts[:: len(pts) // 16] + [pts[-1]]
+            extra["fold_" + name] = {
+                "workload": f"Hq={c2.n_q_heads}, Hkv={c2.n_kv_heads}, d={c2.head_dim}, C={c2.chunk}, "
+                            f"{c2.total_tokens} tokens, 1 layer",
+                "fold_ms": dt * 1e3, "tflops": w2.flops / dt / 1e12, "frac_of_bf16_peak": w2.flops / dt / 1e12 / PEAK_BF16_TFLOPS,
+                "tokens_per_s": c2.total_tokens / dt,
+                "attention_kernel_tflops": w2.flops / (t_ms * 1e-3) / 1e12,
+                "attention_ms": t_ms, "append_ms": a_ms, "merge_ms": m_ms,
+                "algorithmic_GBps": w2.bytes / dt / 1e9,
+                "curve": [{"L_prev": L, "ms": t, "tflops": step_flops(c2, c2.chunk, L) / (t * 1e-3) / 1e12,
+                           "tokens_per_s": c2.chunk / (t * 1e-3),
+                           "algorithmic_GBps": step_bytes(c2, c2.chunk, L) / (t * 1e-3) / 1e9} for L, t in sel],
+            }
+            w2.close()
+    result["extra"] = extra
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

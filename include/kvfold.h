@@ -163,6 +163,18 @@ int kvfold_cache_set_tuning(kvfold_cache_t* cache, int32_t knob, int32_t value);
 int kvfold_cache_plan(const kvfold_cache_t* cache, int32_t n_tokens, int64_t len_after, int32_t* n_workgroups,
                       int32_t* n_splits);
 
+/*
+ * Per-kernel timing for measurements.  Between _begin and _end every step additionally records
+ * HIP events on the step's stream around each of its kernels (append, attention, merge), at most
+ * `max_steps` steps (further steps run untimed).  _end synchronises the device, adds up the
+ * elapsed times in milliseconds, releases the events and returns to normal operation.  Any
+ * output pointer may be NULL.  Event creation makes _begin the only call besides create/destroy
+ * that allocates.
+ */
+int kvfold_cache_profile_begin(kvfold_cache_t* cache, int32_t max_steps);
+int kvfold_cache_profile_end(kvfold_cache_t* cache, int32_t* n_steps /* host */, double* append_ms /* host */,
+                             double* attention_ms /* host */, double* merge_ms /* host */);
+
 /* Static, human-readable name of a status code. */
 const char* kvfold_status_string(int status);
 

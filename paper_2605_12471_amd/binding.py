@@ -80,6 +80,11 @@ def load_library() -> ctypes.CDLL:
     lib.kvfold_cache_set_tuning.restype = ctypes.c_int
     lib.kvfold_cache_plan.argtypes = [vp, i32, i64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.kvfold_cache_plan.restype = ctypes.c_int
+    lib.kvfold_cache_profile_begin.argtypes = [vp, i32]
+    lib.kvfold_cache_profile_begin.restype = ctypes.c_int
+    dp = ctypes.POINTER(ctypes.c_double)
+    lib.kvfold_cache_profile_end.argtypes = [vp, ctypes.POINTER(i32), dp, dp, dp]
+    lib.kvfold_cache_profile_end.restype = ctypes.c_int
     lib.kvfold_status_string.argtypes = [ctypes.c_int]
     lib.kvfold_status_string.restype = ctypes.c_char_p
     lib.kvfold_last_hip_error.argtypes = []
@@ -147,6 +152,19 @@ def kvfold_cache_plan(cache, n_tokens, len_after):
     w, s = ctypes.c_int32(), ctypes.c_int32()
     rc = load_library().kvfold_cache_plan(cache, n_tokens, len_after, ctypes.byref(w), ctypes.byref(s))
     return rc, w.value, s.value
+
+
+def kvfold_cache_profile_begin(cache, max_steps) -> int:
+    return load_library().kvfold_cache_profile_begin(cache, max_steps)
+
+
+def kvfold_cache_profile_end(cache):
+    """Returns (status, n_steps, append_ms, attention_ms, merge_ms)."""
+    n = ctypes.c_int32()
+    a, t, m = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    rc = load_library().kvfold_cache_profile_end(cache, ctypes.byref(n), ctypes.byref(a), ctypes.byref(t),
+                                                 ctypes.byref(m))
+    return rc, n.value, a.value, t.value, m.value
 
 
 def kvfold_status_string(status: int) -> str:
@@ -230,6 +248,18 @@ class KvFoldCache:
         if rc:
             raise KvFoldError(rc, "kvfold_cache_plan")
         return w, s
+
+    def profile_begin(self, max_steps):
+        rc = kvfold_cache_profile_begin(self.handle, max_steps)
+        if rc:
+            raise KvFoldError(rc, "kvfold_cache_profile_begin")
+
+    def profile_end(self):
+        """(n_steps, append_ms, attention_ms, merge_ms) summed over the profiled steps."""
+        rc, n, a, t, m = kvfold_cache_profile_end(self.handle)
+        if rc:
+            raise KvFoldError(rc, "kvfold_cache_profile_end")
+        return n, a, t, m
 
     def view(self, layer=0):
         """(K, V) device tensors [Hkv][capacity][d] aliasing the cache rows of ``layer`` (no copy)."""

@@ -31,6 +31,11 @@ struct kvfold_cache {
   std::vector<int64_t> len;
   int tune_splits;
   int tune_units_per_wave;
+  // optional per-kernel timing: 4 events per step (before append, after append, after attention, after merge)
+  std::vector<hipEvent_t> prof_events;
+  std::vector<char> prof_has_merge;
+  int prof_max_steps = 0;
+  int prof_steps = 0;
 };
 
 namespace {
@@ -265,10 +270,19 @@ int kvfold_step_ex(kvfold_cache_t* c, int layer, const void* q, const void* k_ne
   at.scale_log2e = c->scale * 1.4426950408889634f;
   if (pl.n_splits > 1 && (int64_t)pl.n_splits * n_tokens * f.n_q_heads > c->ws_rows) return KVFOLD_ERR_HIP;  // planner bug guard
 
-  hipError_t e = launch_append(ap, s);
+  hipEvent_t* ev = nullptr;
+  if (c->prof_max_steps > 0 && c->prof_steps < c->prof_max_steps) ev = &c->prof_events[(size_t)c->prof_steps * 4];
+  hipError_t e = hipSuccess;
+  if (ev) {
+    e = hipEventRecord(ev[0], s);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  e = launch_append(ap, s);
   if (e != hipSuccess) return hip_fail(e);
+  if (ev) (void)hipEventRecord(ev[1], s);
   e = (f.dtype == KVFOLD_BF16) ? launch_attn_bf16(at, f.head_dim, pl.units_per_wave, s) : launch_attn_f32(at, f.head_dim, s);
   if (e != hipSuccess) return hip_fail(e);
+  if (ev) (void)hipEventRecord(ev[2], s);
   if (pl.n_splits > 1) {
     CombineParams cp;
     cp.part_o = c->ws_o;
@@ -283,6 +297,11 @@ int kvfold_step_ex(kvfold_cache_t* c, int layer, const void* q, const void* k_ne
     cp.out_is_bf16 = f.dtype == KVFOLD_BF16;
     e = launch_combine(cp, s);
     if (e != hipSuccess) return hip_fail(e);
+  }
+  if (ev) {
+    if (pl.n_splits > 1) (void)hipEventRecord(ev[3], s);
+    c->prof_has_merge[(size_t)c->prof_steps] = pl.n_splits > 1;
+    c->prof_steps++;
   }
   c->len[(size_t)layer] = len_prev + n_tokens;
   return KVFOLD_OK;
@@ -302,6 +321,8 @@ int kvfold_cache_destroy(kvfold_cache_t* c) {
     if (guard.err != hipSuccess) rc = hip_fail(guard.err);
     hipError_t e = hipDeviceSynchronize();
     if (e != hipSuccess) rc = hip_fail(e);
+    for (auto& x : c->prof_events)
+      if (x) (void)hipEventDestroy(x);
     if (c->owns_kv && c->kv) (void)hipFree(c->kv);
     if (c->ws_o) (void)hipFree(c->ws_o);
     if (c->ws_ml) (void)hipFree(c->ws_ml);
@@ -366,6 +387,54 @@ int kvfold_cache_plan(const kvfold_cache_t* c, int32_t n_tokens, int64_t len_aft
   if (n_workgroups) *n_workgroups = pl.n_wgs;
   if (n_splits) *n_splits = pl.n_splits;
   return KVFOLD_OK;
+}
+
+int kvfold_cache_profile_begin(kvfold_cache_t* c, int32_t max_steps) {
+  if (!c || max_steps < 1 || max_steps > (1 << 20) || c->prof_max_steps > 0) return KVFOLD_ERR_INVALID_ARG;
+  DeviceGuard guard(c->cfg.device);
+  if (guard.err != hipSuccess) return hip_fail(guard.err);
+  c->prof_events.assign((size_t)max_steps * 4, nullptr);
+  for (auto& ev : c->prof_events) {
+    hipError_t e = hipEventCreate(&ev);
+    if (e != hipSuccess) {
+      for (auto& x : c->prof_events)
+        if (x) (void)hipEventDestroy(x);
+      c->prof_events.clear();
+      return hip_fail(e);
+    }
+  }
+  c->prof_has_merge.assign((size_t)max_steps, 0);
+  c->prof_max_steps = max_steps;
+  c->prof_steps = 0;
+  return KVFOLD_OK;
+}
+
+int kvfold_cache_profile_end(kvfold_cache_t* c, int32_t* n_steps, double* append_ms, double* attention_ms,
+                             double* merge_ms) {
+  if (!c || c->prof_max_steps == 0) return KVFOLD_ERR_INVALID_ARG;
+  DeviceGuard guard(c->cfg.device);
+  int rc = KVFOLD_OK;
+  hipError_t e = hipDeviceSynchronize();
+  if (e != hipSuccess) rc = hip_fail(e);
+  double a = 0, t = 0, m = 0;
+  for (int i = 0; i < c->prof_steps && rc == KVFOLD_OK; ++i) {
+    hipEvent_t* ev = &c->prof_events[(size_t)i * 4];
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ev[0], ev[1]) == hipSuccess) a += ms;
+    if (hipEventElapsedTime(&ms, ev[1], ev[2]) == hipSuccess) t += ms;
+    if (c->prof_has_merge[(size_t)i] && hipEventElapsedTime(&ms, ev[2], ev[3]) == hipSuccess) m += ms;
+  }
+  if (n_steps) *n_steps = c->prof_steps;
+  if (append_ms) *append_ms = a;
+  if (attention_ms) *attention_ms = t;
+  if (merge_ms) *merge_ms = m;
+  for (auto& x : c->prof_events)
+    if (x) (void)hipEventDestroy(x);
+  c->prof_events.clear();
+  c->prof_has_merge.clear();
+  c->prof_max_steps = 0;
+  c->prof_steps = 0;
+  return rc;
 }
 
 const char* kvfold_status_string(int status) {
