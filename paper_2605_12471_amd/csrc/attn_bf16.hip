@@ -8,25 +8,35 @@
 // Mapping to the machine
 //  * Work unit = (32 consecutive chunk rows, one query head).  A wavefront owns QB units, a
 //    workgroup 4 wavefronts; all units of a workgroup share one KV head, so a K/V tile staged in
-//    LDS is reused across the grouped-query heads.  Units are ordered token-block-major, head-minor,
-//    so the wavefronts of a workgroup see (almost) the same key range and only the last tiles
-//    need the causal mask.
-//  * Per 64-key tile a wavefront forms S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (keys are the M
-//    rows), so each lane ends up with 32 logits of ONE query: row max / row sum are in-lane plus a
-//    single exchange between lanes l and l^32.  The accumulator layout of S^T is, up to a fixed
+//    LDS is reused across the grouped-query heads, and with QB = 2 every K/V fragment read from
+//    LDS feeds two MFMAs (LDS bandwidth, not the matrix pipe, is the limit at QB = 1).  Units are
+//    ordered token-block-major, head-minor, so the wavefronts of a workgroup see (almost) the same
+//    key range and only the last tiles need the causal mask.
+//  * 64-key K/V tiles travel HBM/L2 -> LDS with global_load_lds_dwordx4 (no registers), several
+//    tiles ahead, into rings of NV+1 (K) and NV (V) slots; the XOR swizzle that makes the later
+//    LDS reads conflict-free is applied by choosing which 16-byte chunk each lane fetches.
+//  * Per tile a wavefront forms S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (keys are the M rows),
+//    so each lane ends up with 32 logits of ONE query: row max / row sum are in-lane plus one
+//    exchange between lanes l and l^32.  The accumulator layout of S^T is, up to a fixed
 //    permutation of the keys inside a 16-key slab, the B-operand layout of the next product
 //    O^T = V^T P^T; V^T fragments are read from the row-major V tile with the LDS transpose read
 //    (ds_read_b64_tr_b16) using the same permutation, so P never leaves registers.
+//  * Software pipeline inside the wavefront, in half tiles of 32 keys: while the matrix pipe forms
+//    S^T of half h+1 the vector ALU turns S^T of half h into P (exp2, bf16 pack, row sums); while
+//    it accumulates O^T of half h the vector ALU reduces the row maxima of half h+1.
 //  * Online softmax in base 2 (scale*log2 e folded into one FMA), running max kept stale until it
-//    grows by more than 2^8 (then O and l are rescaled), P rounded to bf16 by the hardware pack
+//    grows by more than 2^16 (then O and l are rescaled), P rounded to bf16 by the hardware pack
 //    convert, row sums accumulated from the ROUNDED values so weights stay a convex combination.
 //  * Optional split of the key range over workgroups: partial (max, sum, O) go to a workspace
 //    and are merged by the combine kernel.
+#include <type_traits>
+
 #include "kvfold_internal.h"
 
 namespace kvfold {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short short4_;
 typedef __attribute__((ext_vector_type(8))) short short8_;
@@ -44,22 +54,58 @@ __device__ __forceinline__ float pair_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-constexpr float kRescaleThreshold = 8.0f;  // log2 units: stale running max tolerated up to 2^8
+// One wavefront-wide 1 KiB copy global -> LDS: lane l's 16 bytes land at lds_base + 16*l.
+// The compiler is not told about the LDS write; ordering is done by hand with wait_vm<> + barrier.
+__device__ __forceinline__ void dma16(const void* g, unsigned lds_base_uniform) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base_uniform) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
-template <int D, int QB>
+// MFMA issued by hand so that the register files are under control: S^T accumulates in VGPRs
+// (the vector ALU reads it next), O^T in AGPRs, and the Q fragments sit in AGPRs as B operands.
+// The compiler does not see these as matrix instructions, so the read-after-MFMA-write distances
+// the hardware needs are kept by construction (see mfma_settle()).
+__device__ __forceinline__ void mfma_qk_first(floatx16& s, const bf16x8& a, const bf16x8& q) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(a), "a"(q));
+}
+__device__ __forceinline__ void mfma_qk(floatx16& s, const bf16x8& a, const bf16x8& q) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(a), "a"(q));
+}
+__device__ __forceinline__ void mfma_pv(floatx16& o, const bf16x8& a, const bf16x8& pfrag) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o) : "v"(a), "v"(pfrag));
+}
+// 48 idle issue cycles tied to a register tuple: everything that reads or writes `x` afterwards
+// is ordered behind a finished matrix pipe (an 8-pass MFMA result is readable 19 cycles after issue).
+__device__ __forceinline__ void mfma_settle_v(floatx16& x) {
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(x));
+}
+__device__ __forceinline__ void mfma_settle_a(floatx16& x) {
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(x));
+}
+
+constexpr float kRescaleThreshold = 16.0f;  // log2 units: stale running max tolerated up to 2^16
+
+template <int D, int QB, int NV>
 __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnParams p) {
-  constexpr int CH = D / 8;         // 16-byte chunks per row
-  constexpr int ROWB = D * 2;       // bytes per row
-  constexpr int BN = kTileKeys;     // 64
-  constexpr int KS = D / 16;        // contraction steps of S^T = K Q^T
-  constexpr int DB = D / 32;        // 32-wide blocks of the head dim in O^T
-  constexpr int LD_IT = BN * CH / 256;
-  constexpr int KSW = CH < 16 ? CH : 16;  // K swizzle period (rows)
+  constexpr int NK = NV + 1;         // K ring slots (K runs half a tile ahead of V in the pipeline)
+  constexpr int CH = D / 8;          // 16-byte chunks per row
+  constexpr int ROWB = D * 2;        // bytes per row
+  constexpr int BN = kTileKeys;      // 64
+  constexpr int KS = D / 16;         // contraction steps of S^T = K Q^T
+  constexpr int DB = D / 32;         // 32-wide blocks of the head dim in O^T
+  constexpr int TILEB = BN * ROWB;   // bytes of one K (or V) tile
+  constexpr int RPS = 64 / CH;       // rows covered by one 1 KiB DMA slab
+  constexpr int SLABS = CH / 4;      // slabs per wavefront per tensor per tile
+  constexpr int LPG = 2 * SLABS;     // DMA instructions per wavefront per tile (K + V)
+  constexpr int KSW = CH < 16 ? CH : 16;  // K swizzle: chunk ^= row % KSW
   constexpr int VSW = CH / 4;             // V swizzle: chunk ^= (row & 3) * VSW
 
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * BN * ROWB];
-  unsigned char* sK = smem;
-  unsigned char* sV = smem + BN * ROWB;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  // rings: K slots [0, NK), V slots [NK, NK + NV)
+  const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(unsigned char, smem);
 
   // ---- which workgroup am I (XCD-aware: contiguous logical ranges per XCD)
   const int per_xcd = gridDim.x / kNumXcd;
@@ -71,17 +117,18 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   const int split = rem / p.wgs_per_head;
   const int ug = p.wgs_per_head - 1 - (rem - split * p.wgs_per_head);  // heaviest (latest rows) first
 
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, hi = l >> 5, m = l & 31;
+  const int tid = threadIdx.x, l = tid & 63, hi = l >> 5, m = l & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int C = p.n_tokens, Hq = p.n_q_heads, G = p.group;
-  const int64_t L = p.len_prev + C;
-  constexpr int UPW = kUnitsPerWg * QB;  // units per workgroup
+  const int Lm1 = (int)(p.len_prev + C - 1);  // last valid cache row
+  constexpr int UPW = kUnitsPerWg * QB;        // units per workgroup
 
   // ---- my units: Q fragments stay in registers for the whole kernel
   bf16x8 qf[QB][KS];
   int tok[QB], head[QB];
   bool store_ok[QB];
-  int64_t my_vis[QB];     // keys visible to this lane's query row
-  int64_t vis_first[QB];  // keys visible to the unit's first row (tiles below need no mask)
+  int my_vis[QB];     // keys visible to this lane's query row
+  int vis_first[QB];  // keys visible to the unit's first row (key blocks entirely below need no mask)
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int u = (ug * kUnitsPerWg + w) * QB + qb;
@@ -91,23 +138,24 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     tok[qb] = tb * kRowsPerUnit + m;
     const int tokc = tok[qb] < C ? tok[qb] : C - 1;
     store_ok[qb] = (u < p.units_per_head) && (tok[qb] < C);
-    my_vis[qb] = p.len_prev + tokc + 1;
-    vis_first[qb] = p.len_prev + (int64_t)tb * kRowsPerUnit + 1;
+    my_vis[qb] = (int)p.len_prev + tokc + 1;
+    vis_first[qb] = (int)p.len_prev + tb * kRowsPerUnit + 1;
     const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ((int64_t)tokc * Hq + head[qb]) * D;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + hi * 8);
   }
+  const int vis_min = vis_first[0];  // units are ordered by token block, so unit 0 has the nearest horizon
 
   // ---- tile range of this workgroup / split
-  int64_t nkeys_wg;
+  int nkeys_wg;
   {
     int ulast = ug * UPW + UPW - 1;
     if (ulast > p.units_per_head - 1) ulast = p.units_per_head - 1;
     int row_hi = (ulast / G) * kRowsPerUnit + kRowsPerUnit - 1;
     if (row_hi > C - 1) row_hi = C - 1;
-    nkeys_wg = p.len_prev + row_hi + 1;
+    nkeys_wg = (int)p.len_prev + row_hi + 1;
   }
-  const int ntiles = (int)((nkeys_wg + BN - 1) / BN);
+  const int ntiles = (nkeys_wg + BN - 1) / BN;
   const int t_begin = split * p.tiles_per_split;
   int t_end = t_begin + p.tiles_per_split;
   if (t_end > ntiles) t_end = ntiles;
@@ -115,45 +163,37 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   const unsigned char* kbase = reinterpret_cast<const unsigned char*>(p.k_cache) + (int64_t)g * p.capacity * ROWB;
   const unsigned char* vbase = reinterpret_cast<const unsigned char*>(p.v_cache) + (int64_t)g * p.capacity * ROWB;
 
-  // ---- per-thread staging slots: chunk ci = it*256 + tid of the tile
-  uint4 kreg[LD_IT], vreg[LD_IT];
-  int ld_row[LD_IT], ld_koff[LD_IT], ld_voff[LD_IT], ld_goff[LD_IT];
-#pragma unroll
-  for (int it = 0; it < LD_IT; ++it) {
-    const int ci = it * 256 + tid;
-    const int row = ci / CH, c = ci % CH;
-    ld_row[it] = row;
-    ld_goff[it] = c * 16;
-    ld_koff[it] = row * ROWB + ((c ^ (row % KSW)) * 16);
-    ld_voff[it] = row * ROWB + ((c ^ ((row & 3) * VSW)) * 16);
-  }
-  auto load_tile = [&](int t) {
-#pragma unroll
-    for (int it = 0; it < LD_IT; ++it) {
-      int64_t grow = (int64_t)t * BN + ld_row[it];
-      if (grow > L - 1) grow = L - 1;  // rows past the cache end are masked anyway; never read them
-      kreg[it] = *reinterpret_cast<const uint4*>(kbase + grow * ROWB + ld_goff[it]);
-      vreg[it] = *reinterpret_cast<const uint4*>(vbase + grow * ROWB + ld_goff[it]);
-    }
+  // ---- DMA addressing: wavefront w moves slabs w, w+4, ...; lane l lands at chunk (l % CH) of row
+  // slab*RPS + l / CH and therefore fetches the chunk that the swizzle maps there.
+  const int dma_row0 = w * RPS + l / CH;  // + i * 4 * RPS for slab i
+  const int dma_kc = (((l % CH) ^ (dma_row0 % KSW))) * 16;
+  const int dma_vc = (((l % CH) ^ ((dma_row0 & 3) * VSW))) * 16;
+  auto issue_slab = [&](const unsigned char* base, int cbytes, int t, int i, unsigned slot_base) {
+    int grow = t * BN + dma_row0 + i * 4 * RPS;
+    grow = grow < Lm1 ? grow : Lm1;  // rows past the cache end are masked anyway; never read them
+    dma16(base + (int64_t)grow * ROWB + cbytes, slot_base + (unsigned)((w + 4 * i) * 1024));
   };
-  auto store_tile = [&]() {
+  auto issue_k = [&](int t) {
 #pragma unroll
-    for (int it = 0; it < LD_IT; ++it) {
-      *reinterpret_cast<uint4*>(sK + ld_koff[it]) = kreg[it];
-      *reinterpret_cast<uint4*>(sV + ld_voff[it]) = vreg[it];
-    }
+    for (int i = 0; i < SLABS; ++i) issue_slab(kbase, dma_kc, t, i, lds0 + (unsigned)((t % NK) * TILEB));
+  };
+  auto issue_v = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < SLABS; ++i) issue_slab(vbase, dma_vc, t, i, lds0 + (unsigned)((NK + t % NV) * TILEB));
   };
 
-  // ---- LDS read addresses
-  // K fragment (A operand of S^T): row kb*32+m, chunk ks*2+hi (swizzled by row % KSW = m % KSW)
-  const int k_row_off = m * ROWB;
-  const int k_sw = m % KSW;
-  // V^T fragment via transpose read: lane i of a 16-lane block supplies row (i/4), 4 columns
+  // ---- LDS read offsets (per lane, without the ring slot)
+  // K fragment (A operand of S^T): row kb*32+m, chunk ks*2+hi, swizzled by row % KSW = m % KSW
+  int koff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = m * ROWB + (((ks * 2 + hi) ^ (m % KSW)) * 16);
+  // V^T fragment via transpose read: lane i of a 16-lane block supplies row (i/4) of a 4-row group and 4 columns
   const int i16 = l & 15, b2 = (l >> 4) & 1;
-  const int v_row = 4 * hi + (i16 >> 2);                       // + 16*t (+8)
-  const int v_chunk_lo = 2 * b2 + ((i16 & 3) >> 1);           // + 4*db, then swizzled
-  const int v_inner = 8 * (i16 & 1);
-  const int v_sw = (v_row & 3) * VSW;
+  const int v_row = 4 * hi + (i16 >> 2);  // + 16*tt (+8)
+  int voff[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+    voff[db] = v_row * ROWB + (((4 * db + 2 * b2 + ((i16 & 3) >> 1)) ^ ((v_row & 3) * VSW)) * 16) + 8 * (i16 & 1);
 
   // ---- running state
   floatx16 o[QB][DB];
@@ -169,100 +209,223 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   }
   const float sc = p.scale_log2e;
 
-  if (t_begin < t_end) load_tile(t_begin);
-  for (int t = t_begin; t < t_end; ++t) {
-    __syncthreads();  // everyone finished reading the previous tile
-    store_tile();
-    __syncthreads();
-    if (t + 1 < t_end) load_tile(t + 1);  // in flight while this tile is consumed
-
-    // ---- S^T = K Q^T
-    floatx16 s[QB][2];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[qb][kb][r] = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a =
-            *reinterpret_cast<const bf16x8*>(sK + kb * 32 * ROWB + k_row_off + (((ks * 2 + hi) ^ k_sw) * 16));
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[qb][kb], 0, 0, 0);
-      }
-    }
-
-    // ---- online softmax (per lane: one query, 32 keys)
-    bf16x8 pb[QB][4];
-    const int64_t tile_key0 = (int64_t)t * BN;
+  // ---- building blocks of the software pipeline --------------------------------------------
+  auto k_frag = [&](int hh, int ks) -> bf16x8 {
+    return *reinterpret_cast<const bf16x8*>(smem + ((hh >> 1) % NK) * TILEB + (hh & 1) * 32 * ROWB + koff[ks]);
+  };
+  auto v_frag = [&](int hh, int tt, int db) -> bf16x8 {
+    const unsigned char* a0 = smem + (NK + (hh >> 1) % NV) * TILEB + (hh & 1) * 32 * ROWB + 16 * tt * ROWB + voff[db];
+    const short4_ lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0));
+    const short4_ hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0 + 8 * ROWB));
+    const short8_ a8 = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, a8);
+  };
+  // causal mask of the 32-key half hh
+  auto mask_half = [&](floatx16 (&s)[QB], int hh) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      const bool need_mask = tile_key0 + BN > vis_first[qb];  // wave-uniform
-      if (need_mask) {
+      if (hh * 32 + 32 > vis_first[qb]) {  // wave-uniform
+        const int rel = my_vis[qb] - hh * 32;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int64_t j = tile_key0 + kb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
-            if (j >= my_vis[qb]) s[qb][kb][r] = -INFINITY;
-          }
+        for (int r = 0; r < 16; ++r)
+          if (8 * (r >> 2) + 4 * hi + (r & 3) >= rel) s[qb][r] = -INFINITY;
       }
-      float mx = s[qb][0][0];
+    }
+  };
+  // raise the running max (rescaling O and l) only when it lags the new row max by more than 2^16
+  auto rescale = [&](const float (&mx)[QB]) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[qb][kb][r]);
-      mx = pair_max(mx) * sc;  // sc > 0, so the max commutes with the scaling
-      if (__any(mx > m_run[qb] + kRescaleThreshold)) {
-        const float m2 = fmaxf(m_run[qb], mx);
+    for (int qb = 0; qb < QB; ++qb) {
+      const float mnew = pair_max(mx[qb]) * sc;  // sc > 0, so the max commutes with the scaling
+      if (__builtin_expect(__any(mnew > m_run[qb] + kRescaleThreshold), 0)) {
+        const float m2 = fmaxf(m_run[qb], mnew);
         const float alpha = (m2 == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_run[qb] - m2);
         m_run[qb] = m2;
         l_run[qb] *= alpha;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db) {
+          mfma_settle_a(o[qb][db]);
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
-      }
-      const float m_use = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
-      bf16x2 ones;
-      ones[0] = (__bf16)1.0f;
-      ones[1] = (__bf16)1.0f;
-      float lsum = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[qb][kb][r], sc, -m_use));
-          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[qb][kb][r + 1], sc, -m_use));
-          bf16x2 pk;
-          pk[0] = (__bf16)p0;
-          pk[1] = (__bf16)p1;
-          lsum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lsum, false);
-          const int tt = kb * 2 + (r >> 3), e = r & 7;
-          pb[qb][tt][e] = pk[0];
-          pb[qb][tt][e + 1] = pk[1];
         }
-      l_run[qb] += lsum;
-    }
-
-    // ---- O^T += V^T P^T
-#pragma unroll
-    for (int tt = 0; tt < 4; ++tt) {
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const unsigned char* a0 =
-            sV + (16 * tt + v_row) * ROWB + (((4 * db + v_chunk_lo) ^ v_sw) * 16) + v_inner;
-        const short4_ lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0));
-        const short4_ hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0 + 8 * ROWB));
-        const short8_ a8 = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 a = __builtin_bit_cast(bf16x8, a8);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][tt], o[qb][db], 0, 0, 0);
       }
     }
+  };
+  auto rowmax_all = [&](floatx16 (&s)[QB], float (&mx)[QB]) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float a = fmaxf(s[qb][0], s[qb][1]);
+#pragma unroll
+      for (int r = 2; r < 16; r += 2) a = fmaxf(fmaxf(a, s[qb][r]), s[qb][r + 1]);
+      mx[qb] = a;
+    }
+  };
+
+  constexpr int NS1 = KS;      // slots of phase 1 (one K fragment, QB MFMAs each); equals LPG
+  constexpr int NS2 = 2 * DB;  // slots of phase 2 (one V^T fragment, QB MFMAs each)
+  static_assert(NS1 == LPG, "one DMA per phase-1 slot");
+  // Vector-ALU work of one step is dealt out behind individual MFMAs so that it hides under the
+  // matrix pipe.  The unit is a pair of logits (2 fma, 2 exp2, 1 pack, 1 dot2).  Pairs are
+  // numbered slab 0 first (keys 0..15 of the half, needed by the first half of phase 2), then
+  // slab 1 (needed by the second half of phase 2).
+  constexpr int NP = QB * 8;            // pairs per step
+  constexpr int M1 = NS1 * QB;          // MFMAs of phase 1
+  constexpr int H2 = NS2 * QB / 2;      // MFMAs of each half of phase 2
+  constexpr int P1 = QB * 6;            // pairs placed in phase 1 (all of slab 0, half of slab 1)
+  static_assert(P1 >= QB * 4 && P1 <= NP, "slab 0 must be complete before phase 2");
+  floatx16 sA[QB], sB[QB];
+  // One pipeline step for half hh.  On entry s_cur holds S^T of half hh (masked, its row max already
+  // folded into m_run).  Phase 1: the matrix pipe forms S^T of half hh+1 into s_next; phase 2: it
+  // accumulates O^T += V^T P^T of half hh.  MASKED selects the rare variant for halves hh+1 that
+  // reach past the causal horizon (mask, then row max, after the matrix work).
+  auto step = [&](floatx16 (&s_cur)[QB], floatx16 (&s_next)[QB], int hh, auto tile_start_tag, auto masked_tag) {
+    constexpr bool TILE_START = decltype(tile_start_tag)::value;
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    const int t = hh >> 1;
+    if (TILE_START) {
+      // K[t+1] and V[t] were issued NV-1 tiles ago: they are the oldest group in flight
+      wait_vm<(NV - 2) * LPG>();
+      __builtin_amdgcn_s_barrier();  // ... for every wavefront; also: everyone is done reading K[t-1], V[t-1]
+    }
+    bf16x2 ones;
+    ones[0] = (__bf16)1.0f;
+    ones[1] = (__bf16)1.0f;
+    float m_use[QB], lsum[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      m_use[qb] = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
+      lsum[qb] = 0.f;
+    }
+    bf16x8 pb[QB][2];
+    // pairs [k0, k1): P = 2^(S*sc - m) rounded to bf16, row sums of the rounded values
+    auto softmax_pairs = [&](int k0, int k1) {
+#pragma unroll
+      for (int k = k0; k < k1; ++k) {
+        const int slab = k / (QB * 4), kk = k % (QB * 4);
+        const int qb = kk >> 2, j = 2 * (kk & 3), r = 8 * slab + j;
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[qb][r], sc, -m_use[qb]));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[qb][r + 1], sc, -m_use[qb]));
+        bf16x2 pk;
+        pk[0] = (__bf16)p0;
+        pk[1] = (__bf16)p1;
+        lsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lsum[qb], false);
+        pb[qb][slab][j] = pk[0];
+        pb[qb][slab][j + 1] = pk[1];
+      }
+    };
+    // ---- phase 1
+    bf16x8 ka[2];
+    ka[0] = k_frag(hh + 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < NS1; ++ks) {
+      if (ks + 1 < NS1) ka[(ks + 1) & 1] = k_frag(hh + 1, ks + 1);
+      if (TILE_START) {  // refill the slots the barrier has just freed: K[t-1]'s and V[t-1]'s
+        if (ks < SLABS) issue_slab(kbase, dma_kc, t + NV, ks, lds0 + (unsigned)(((t + NV) % NK) * TILEB));
+        else issue_slab(vbase, dma_vc, t + NV - 1, ks - SLABS, lds0 + (unsigned)((NK + (t + NV - 1) % NV) * TILEB));
+      }
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const int i = ks * QB + qb;  // MFMA index within phase 1
+        if (ks == 0)
+          mfma_qk_first(s_next[qb], ka[ks & 1], qf[qb][ks]);
+        else
+          mfma_qk(s_next[qb], ka[ks & 1], qf[qb][ks]);
+        __builtin_amdgcn_sched_barrier(0);
+        softmax_pairs((i * P1) / M1, ((i + 1) * P1) / M1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // ---- phase 2
+    float mx[QB];
+    bf16x8 va[2];
+    va[0] = v_frag(hh, 0, 0);
+    asm volatile("s_nop 1" ::: "memory");  // vector-ALU results (P) settle before the matrix pipe reads them
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int sl = 0; sl < NS2; ++sl) {
+      const int tt = sl / DB, db = sl % DB;
+      if (sl + 1 < NS2) va[(sl + 1) & 1] = v_frag(hh, (sl + 1) / DB, (sl + 1) % DB);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const int i = sl * QB + qb;  // MFMA index within phase 2
+        mfma_pv(o[qb][db], va[sl & 1], pb[qb][tt]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i < H2) {
+          softmax_pairs(P1 + (i * (NP - P1)) / H2, P1 + ((i + 1) * (NP - P1)) / H2);
+        } else if (!MASKED) {
+          // row maxima of s_next: its MFMAs were issued at least H2 MFMAs ago
+#pragma unroll
+          for (int k = ((i - H2) * NP) / H2; k < ((i - H2 + 1) * NP) / H2; ++k) {
+            const int q2 = k >> 3, r = 2 * (k & 7);
+            if (r == 0)
+              mx[q2] = fmaxf(s_next[q2][0], s_next[q2][1]);
+            else
+              mx[q2] = fmaxf(fmaxf(mx[q2], s_next[q2][r]), s_next[q2][r + 1]);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) l_run[qb] += lsum[qb];
+    if (MASKED) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
+      mask_half(s_next, hh + 1);
+      rowmax_all(s_next, mx);
+    }
+    rescale(mx);
+  };
+
+  if (t_begin < t_end) {
+    // prologue: K[t_begin], then the groups {K[t+1+j], V[t+j]} the steady state expects in flight
+    issue_k(t_begin);
+#pragma unroll
+    for (int j = 0; j < NV - 1; ++j) {
+      issue_k(t_begin + 1 + j);
+      issue_v(t_begin + j);
+    }
+    wait_vm<(NV - 1) * LPG>();
+    __builtin_amdgcn_s_barrier();
+    {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 a = k_frag(2 * t_begin, ks);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          if (ks == 0)
+            mfma_qk_first(sA[qb], a, qf[qb][ks]);
+          else
+            mfma_qk(sA[qb], a, qf[qb][ks]);
+        }
+      }
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) mfma_settle_v(sA[qb]);
+      if (t_begin * BN + 32 > vis_min) mask_half(sA, 2 * t_begin);
+      float mx[QB];
+      rowmax_all(sA, mx);
+      rescale(mx);
+    }
+    // Tiles whose two steps only produce halves entirely below the nearest causal horizon take the
+    // fast variant: step 2t+1 produces half 2t+2 = keys [64t+64, 64t+96), so it needs 64t+96 <= vis_min.
+    int t_fast = (vis_min - 96) / BN + 1;  // first tile that is not fast (vis_min >= 1)
+    if (vis_min < 96) t_fast = 0;
+    if (t_fast > t_end) t_fast = t_end;
+    int t = t_begin;
+    for (; t < t_fast; ++t) {
+      step(sA, sB, 2 * t, std::true_type{}, std::false_type{});
+      step(sB, sA, 2 * t + 1, std::false_type{}, std::false_type{});
+    }
+    for (; t < t_end; ++t) {
+      step(sA, sB, 2 * t, std::true_type{}, std::true_type{});
+      step(sB, sA, 2 * t + 1, std::false_type{}, std::true_type{});
+    }
+    wait_vm<0>();  // nothing of ours may still be writing LDS when the workgroup retires
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) mfma_settle_a(o[qb][db]);
   }
 
   // ---- epilogue
@@ -279,7 +442,6 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
-          typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
           bf16x4 v;
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[qb][db][rg * 4 + e] * inv);
@@ -305,15 +467,23 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   }
 }
 
-template <int D, int QB>
+template <int D, int QB, int NV>
 static hipError_t launch_one(const AttnParams& p, hipStream_t s) {
-  hipLaunchKernelGGL((attn_bf16_kernel<D, QB>), dim3(padded_grid(p.n_wgs)), dim3(256), 0, s, p);
+  constexpr int lds_bytes = (2 * NV + 1) * kTileKeys * D * 2;
+  static bool attr_set = false;  // idempotent; a benign race at worst sets it twice
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, QB, NV>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((attn_bf16_kernel<D, QB, NV>), dim3(padded_grid(p.n_wgs)), dim3(256), lds_bytes, s, p);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, int qb, hipStream_t s) {
-  if (head_dim == 128) return qb == 2 ? launch_one<128, 2>(p, s) : launch_one<128, 1>(p, s);
-  if (head_dim == 64) return qb == 2 ? launch_one<64, 2>(p, s) : launch_one<64, 1>(p, s);
+  if (head_dim == 128) return qb == 2 ? launch_one<128, 2, 3>(p, s) : launch_one<128, 1, 2>(p, s);
+  if (head_dim == 64) return qb == 2 ? launch_one<64, 2, 3>(p, s) : launch_one<64, 1, 2>(p, s);
   return hipErrorInvalidValue;
 }
 

@@ -60,7 +60,7 @@ int validate_config(const kvfold_config_t* c) {
   if (c->head_dim != 64 && c->head_dim != 128) return KVFOLD_ERR_UNSUPPORTED;
   if (c->n_q_heads % c->n_kv_heads) return KVFOLD_ERR_UNSUPPORTED;
   // sizes the kernels index with 32-bit row counts / 64-bit byte offsets
-  if (c->capacity_tokens > (int64_t)1 << 31 || (int64_t)c->chunk_tokens * c->n_q_heads > (int64_t)1 << 28)
+  if (c->capacity_tokens > (int64_t)1 << 30 || (int64_t)c->chunk_tokens * c->n_q_heads > (int64_t)1 << 28)
     return KVFOLD_ERR_UNSUPPORTED;
   if (c->chunk_tokens > c->capacity_tokens) return KVFOLD_ERR_INVALID_ARG;
   return KVFOLD_OK;
