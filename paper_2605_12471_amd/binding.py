@@ -16,7 +16,7 @@ TUNE_SPLITS = 0
 TUNE_UNITS_PER_WAVE = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "_lib", "libkvfold.so")
+_LIB_PATH = os.environ.get("KVFOLD_LIB_PATH") or os.path.join(_HERE, "_lib", "libkvfold.so")
 _lib = None
 
 

@@ -24,9 +24,12 @@
 //  * Software pipeline inside the wavefront, in half tiles of 32 keys: while the matrix pipe forms
 //    S^T of half h+1 the vector ALU turns S^T of half h into P (exp2, bf16 pack, row sums); while
 //    it accumulates O^T of half h the vector ALU reduces the row maxima of half h+1.
-//  * Online softmax in base 2 (scale*log2 e folded into one FMA), running max kept stale until it
-//    grows by more than 2^16 (then O and l are rescaled), P rounded to bf16 by the hardware pack
-//    convert, row sums accumulated from the ROUNDED values so weights stay a convex combination.
+//  * Online softmax in base 2 with ONE vector instruction per logit: the queries are multiplied by
+//    scale*log2(e) once (and rounded to bf16 again), and the S^T accumulators start from -m (the
+//    running row max) instead of 0, so the matrix pipe delivers S*scale*log2e - m and P is a bare
+//    exp2.  The running max is kept stale until it lags by more than 2^16 (then O, l and the
+//    in-flight logits are corrected); P is rounded to bf16 by the hardware pack convert and row sums
+//    are accumulated from the ROUNDED values so the weights stay a convex combination.
 //  * Optional split of the key range over workgroups: partial (max, sum, O) go to a workspace
 //    and are merged by the combine kernel.
 #include <type_traits>
@@ -41,6 +44,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short short4_;
 typedef __attribute__((ext_vector_type(8))) short short8_;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
+typedef __attribute__((ext_vector_type(4))) unsigned uintx4;
 
 #define LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(p))
 
@@ -54,10 +58,12 @@ __device__ __forceinline__ float pair_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// One wavefront-wide 1 KiB copy global -> LDS: lane l's 16 bytes land at lds_base + 16*l.
-// The compiler is not told about the LDS write; ordering is done by hand with wait_vm<> + barrier.
-__device__ __forceinline__ void dma16(const void* g, unsigned lds_base_uniform) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base_uniform) : "memory");
+// One wavefront-wide 1 KiB copy global -> LDS: lane l's 16 bytes, read from base + off, land at
+// lds_base + 16*l.  The compiler is not told about the LDS write; ordering is done by hand with
+// wait_vm<> + barrier.
+__device__ __forceinline__ void dma16(const unsigned char* base_uniform, unsigned off, unsigned lds_base_uniform) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base_uniform), "s"(lds_base_uniform)
+               : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
@@ -67,9 +73,9 @@ __device__ __forceinline__ void wait_vm() {
 // MFMA issued by hand so that the register files are under control: S^T accumulates in VGPRs
 // (the vector ALU reads it next), O^T in AGPRs, and the Q fragments sit in AGPRs as B operands.
 // The compiler does not see these as matrix instructions, so the read-after-MFMA-write distances
-// the hardware needs are kept by construction (see mfma_settle()).
-__device__ __forceinline__ void mfma_qk_first(floatx16& s, const bf16x8& a, const bf16x8& q) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(a), "a"(q));
+// the hardware needs are kept by construction (see mfma_settle_*()).
+__device__ __forceinline__ void mfma_qk_first(floatx16& s, const bf16x8& a, const bf16x8& q, const floatx16& c0) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(s) : "v"(a), "a"(q), "v"(c0));
 }
 __device__ __forceinline__ void mfma_qk(floatx16& s, const bf16x8& a, const bf16x8& q) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(a), "a"(q));
@@ -86,6 +92,15 @@ __device__ __forceinline__ void mfma_settle_a(floatx16& x) {
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(x));
 }
 
+#ifndef KVFOLD_LDS_PF
+#define KVFOLD_LDS_PF 1  // LDS fragment reads run this many slots ahead of the MFMAs that use them
+#endif
+#ifndef KVFOLD_P1_EIGHTHS
+#define KVFOLD_P1_EIGHTHS 6  // pairs of phase 1 = QB * this (4..8)
+#endif
+#ifndef KVFOLD_NV2
+#define KVFOLD_NV2 3  // V ring slots of the two-units-per-wave kernel (K ring has one more)
+#endif
 constexpr float kRescaleThreshold = 16.0f;  // log2 units: stale running max tolerated up to 2^16
 
 template <int D, int QB, int NV>
@@ -97,6 +112,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   constexpr int KS = D / 16;         // contraction steps of S^T = K Q^T
   constexpr int DB = D / 32;         // 32-wide blocks of the head dim in O^T
   constexpr int TILEB = BN * ROWB;   // bytes of one K (or V) tile
+  constexpr int HALFB = 32 * ROWB;   // bytes of a 32-key half tile
   constexpr int RPS = 64 / CH;       // rows covered by one 1 KiB DMA slab
   constexpr int SLABS = CH / 4;      // slabs per wavefront per tensor per tile
   constexpr int LPG = 2 * SLABS;     // DMA instructions per wavefront per tile (K + V)
@@ -122,8 +138,9 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   const int C = p.n_tokens, Hq = p.n_q_heads, G = p.group;
   const int Lm1 = (int)(p.len_prev + C - 1);  // last valid cache row
   constexpr int UPW = kUnitsPerWg * QB;        // units per workgroup
+  const float sc = p.scale_log2e;
 
-  // ---- my units: Q fragments stay in registers for the whole kernel
+  // ---- my units: Q fragments, pre-multiplied by scale*log2(e), stay in registers for the whole kernel
   bf16x8 qf[QB][KS];
   int tok[QB], head[QB];
   bool store_ok[QB];
@@ -142,7 +159,12 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     vis_first[qb] = (int)p.len_prev + tb * kRowsPerUnit + 1;
     const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ((int64_t)tokc * Hq + head[qb]) * D;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + hi * 8);
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + hi * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[qb][ks][e] = (__bf16)((float)raw[e] * sc);
+      asm volatile("" : "+a"(qf[qb][ks]));  // park the fragment in the AGPR file, where the MFMAs read it
+    }
   }
   const int vis_min = vis_first[0];  // units are ordered by token block, so unit 0 has the nearest horizon
 
@@ -164,64 +186,82 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   const unsigned char* vbase = reinterpret_cast<const unsigned char*>(p.v_cache) + (int64_t)g * p.capacity * ROWB;
 
   // ---- DMA addressing: wavefront w moves slabs w, w+4, ...; lane l lands at chunk (l % CH) of row
-  // slab*RPS + l / CH and therefore fetches the chunk that the swizzle maps there.
+  // slab*RPS + l / CH and therefore fetches the chunk that the swizzle maps there.  Offsets from
+  // the head's base are 32-bit (the host checks capacity * row bytes < 2^32).
   const int dma_row0 = w * RPS + l / CH;  // + i * 4 * RPS for slab i
-  const int dma_kc = (((l % CH) ^ (dma_row0 % KSW))) * 16;
-  const int dma_vc = (((l % CH) ^ ((dma_row0 & 3) * VSW))) * 16;
-  auto issue_slab = [&](const unsigned char* base, int cbytes, int t, int i, unsigned slot_base) {
-    int grow = t * BN + dma_row0 + i * 4 * RPS;
-    grow = grow < Lm1 ? grow : Lm1;  // rows past the cache end are masked anyway; never read them
-    dma16(base + (int64_t)grow * ROWB + cbytes, slot_base + (unsigned)((w + 4 * i) * 1024));
+  const unsigned dma_kc = (unsigned)(((l % CH) ^ (dma_row0 % KSW)) * 16);
+  const unsigned dma_vc = (unsigned)(((l % CH) ^ ((dma_row0 & 3) * VSW)) * 16);
+  const unsigned dma_koff = (unsigned)dma_row0 * ROWB + dma_kc;  // lane part of an unclamped offset
+  const unsigned dma_voff = (unsigned)dma_row0 * ROWB + dma_vc;
+  // slab i of tile t of K (is_v = false) or V; CLAMP redirects rows past the cache end to the last
+  // valid row (they are masked anyway, but are never read from memory)
+  auto issue_slab = [&](bool is_v, int t, int i, auto clamp_tag) __attribute__((always_inline)) {
+    constexpr bool CLAMP = decltype(clamp_tag)::value;
+    const unsigned slot = is_v ? (unsigned)(NK + t % NV) : (unsigned)(t % NK);
+    const unsigned lds = lds0 + slot * TILEB + (unsigned)((w + 4 * i) * 1024);
+    unsigned off;
+    if (CLAMP) {
+      unsigned grow = (unsigned)(t * BN + dma_row0 + i * 4 * RPS);
+      grow = grow < (unsigned)Lm1 ? grow : (unsigned)Lm1;
+      off = grow * ROWB + (is_v ? dma_vc : dma_kc);
+    } else {
+      off = (is_v ? dma_voff : dma_koff) + (unsigned)(t * BN + i * 4 * RPS) * ROWB;
+    }
+    dma16(is_v ? vbase : kbase, off, lds);
   };
-  auto issue_k = [&](int t) {
+  auto issue_k = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < SLABS; ++i) issue_slab(kbase, dma_kc, t, i, lds0 + (unsigned)((t % NK) * TILEB));
+    for (int i = 0; i < SLABS; ++i) issue_slab(false, t, i, std::true_type{});
   };
-  auto issue_v = [&](int t) {
+  auto issue_v = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < SLABS; ++i) issue_slab(vbase, dma_vc, t, i, lds0 + (unsigned)((NK + t % NV) * TILEB));
+    for (int i = 0; i < SLABS; ++i) issue_slab(true, t, i, std::true_type{});
   };
 
   // ---- LDS read offsets (per lane, without the ring slot)
   // K fragment (A operand of S^T): row kb*32+m, chunk ks*2+hi, swizzled by row % KSW = m % KSW
-  int koff[KS];
+  unsigned koff[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) koff[ks] = m * ROWB + (((ks * 2 + hi) ^ (m % KSW)) * 16);
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = (unsigned)(m * ROWB + (((ks * 2 + hi) ^ (m % KSW)) * 16));
   // V^T fragment via transpose read: lane i of a 16-lane block supplies row (i/4) of a 4-row group and 4 columns
   const int i16 = l & 15, b2 = (l >> 4) & 1;
   const int v_row = 4 * hi + (i16 >> 2);  // + 16*tt (+8)
-  int voff[DB];
+  unsigned voff[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
-    voff[db] = v_row * ROWB + (((4 * db + 2 * b2 + ((i16 & 3) >> 1)) ^ ((v_row & 3) * VSW)) * 16) + 8 * (i16 & 1);
+    voff[db] = (unsigned)(v_row * ROWB + (((4 * db + 2 * b2 + ((i16 & 3) >> 1)) ^ ((v_row & 3) * VSW)) * 16) + 8 * (i16 & 1));
+  // offsets including the ring slot of the tile currently being read; refreshed once per tile
+  unsigned kaddr[KS], vaddr[DB];
 
   // ---- running state
-  floatx16 o[QB][DB];
+  floatx16 o[QB][DB];   // O^T accumulators (AGPRs)
+  floatx16 negm[QB];    // -m (0 while no key has been seen) in every element: start value of S^T
   float m_run[QB], l_run[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     m_run[qb] = -INFINITY;
     l_run[qb] = 0.f;
 #pragma unroll
+    for (int r = 0; r < 16; ++r) negm[qb][r] = 0.f;
+#pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
   }
-  const float sc = p.scale_log2e;
 
   // ---- building blocks of the software pipeline --------------------------------------------
-  auto k_frag = [&](int hh, int ks) -> bf16x8 {
-    return *reinterpret_cast<const bf16x8*>(smem + ((hh >> 1) % NK) * TILEB + (hh & 1) * 32 * ROWB + koff[ks]);
+  auto k_frag = [&](int ks, int imm) __attribute__((always_inline)) -> bf16x8 {
+    return *reinterpret_cast<const bf16x8*>(smem + kaddr[ks] + imm);
   };
-  auto v_frag = [&](int hh, int tt, int db) -> bf16x8 {
-    const unsigned char* a0 = smem + (NK + (hh >> 1) % NV) * TILEB + (hh & 1) * 32 * ROWB + 16 * tt * ROWB + voff[db];
+  auto v_frag = [&](int tt, int db, int imm) __attribute__((always_inline)) -> bf16x8 {
+    const unsigned char* a0 = smem + vaddr[db] + imm + 16 * tt * ROWB;
     const short4_ lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0));
     const short4_ hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0 + 8 * ROWB));
     const short8_ a8 = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, a8);
   };
   // causal mask of the 32-key half hh
-  auto mask_half = [&](floatx16 (&s)[QB], int hh) {
+  auto mask_half = [&](floatx16 (&s)[QB], int hh) __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       if (hh * 32 + 32 > vis_first[qb]) {  // wave-uniform
@@ -232,26 +272,45 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       }
     }
   };
-  // raise the running max (rescaling O and l) only when it lags the new row max by more than 2^16
-  auto rescale = [&](const float (&mx)[QB]) {
+  // mx[] holds the row maxima of a half whose logits are already relative to the running max, i.e.
+  // by how much the max would grow.  The running max is raised only when it lags by more than
+  // 2^16 (or has never been set).  The decision (cross-lane max, compare) is taken early, under
+  // the matrix pipe; the branch comes later.
+  auto rescale_decide = [&](const float (&mx)[QB], float (&dm)[QB]) __attribute__((always_inline)) -> bool {
+    int need = 0;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      const float mnew = pair_max(mx[qb]) * sc;  // sc > 0, so the max commutes with the scaling
-      if (__builtin_expect(__any(mnew > m_run[qb] + kRescaleThreshold), 0)) {
-        const float m2 = fmaxf(m_run[qb], mnew);
-        const float alpha = (m2 == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_run[qb] - m2);
-        m_run[qb] = m2;
-        l_run[qb] *= alpha;
+      dm[qb] = pair_max(mx[qb]);
+      // no short-circuit: plain lane-wise compares, one wave-wide reduction at the end
+      need |= (int)(dm[qb] > kRescaleThreshold) | ((int)(m_run[qb] == -INFINITY) & (int)(dm[qb] > -INFINITY));
+    }
+    return __any(need);
+  };
+  // s holds the logits of the half the maxima came from: they were formed against the old max
+  auto rescale_apply = [&](const float (&dm)[QB], floatx16 (&s)[QB]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          mfma_settle_a(o[qb][db]);
+    for (int qb = 0; qb < QB; ++qb) {
+      const float cur = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
+      const float m2 = fmaxf(m_run[qb], cur + dm[qb]);
+      const float use = (m2 == -INFINITY) ? 0.f : m2;
+      const float delta = use - cur;
+      const float alpha = __builtin_amdgcn_exp2f(-delta);
+      m_run[qb] = m2;
+      l_run[qb] *= alpha;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
-        }
+      for (int r = 0; r < 16; ++r) {
+        negm[qb][r] = -use;
+        s[qb][r] -= delta;
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        mfma_settle_a(o[qb][db]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
       }
     }
   };
-  auto rowmax_all = [&](floatx16 (&s)[QB], float (&mx)[QB]) {
+  auto rowmax_all = [&](floatx16 (&s)[QB], float (&mx)[QB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       float a = fmaxf(s[qb][0], s[qb][1]);
@@ -265,104 +324,123 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   constexpr int NS2 = 2 * DB;  // slots of phase 2 (one V^T fragment, QB MFMAs each)
   static_assert(NS1 == LPG, "one DMA per phase-1 slot");
   // Vector-ALU work of one step is dealt out behind individual MFMAs so that it hides under the
-  // matrix pipe.  The unit is a pair of logits (2 fma, 2 exp2, 1 pack, 1 dot2).  Pairs are
-  // numbered slab 0 first (keys 0..15 of the half, needed by the first half of phase 2), then
-  // slab 1 (needed by the second half of phase 2).
+  // matrix pipe.  The unit is a pair of logits (2 exp2, 1 pack, 1 dot2).  Pairs are numbered slab 0
+  // first (keys 0..15 of the half, needed by the first half of phase 2), then slab 1 (needed by
+  // the second half of phase 2).
   constexpr int NP = QB * 8;            // pairs per step
   constexpr int M1 = NS1 * QB;          // MFMAs of phase 1
-  constexpr int H2 = NS2 * QB / 2;      // MFMAs of each half of phase 2
-  constexpr int P1 = QB * 6;            // pairs placed in phase 1 (all of slab 0, half of slab 1)
+  constexpr int M2 = NS2 * QB;          // MFMAs of phase 2
+  constexpr int H2 = M2 / 2;
+  constexpr int P1 = QB * KVFOLD_P1_EIGHTHS;  // pairs placed in phase 1 (all of slab 0, part of slab 1)
   static_assert(P1 >= QB * 4 && P1 <= NP, "slab 0 must be complete before phase 2");
+  constexpr int RM0 = M2 >= 8 ? 2 : 1, RM1 = M2 - RM0;  // phase-2 MFMA slots that carry the row-max work / the decision
+  static_assert(RM1 > RM0 && RM1 < M2, "phase 2 too short");
+  constexpr int PF = KVFOLD_LDS_PF;
+
   floatx16 sA[QB], sB[QB];
-  // One pipeline step for half hh.  On entry s_cur holds S^T of half hh (masked, its row max already
-  // folded into m_run).  Phase 1: the matrix pipe forms S^T of half hh+1 into s_next; phase 2: it
-  // accumulates O^T += V^T P^T of half hh.  MASKED selects the rare variant for halves hh+1 that
-  // reach past the causal horizon (mask, then row max, after the matrix work).
-  auto step = [&](floatx16 (&s_cur)[QB], floatx16 (&s_next)[QB], int hh, auto tile_start_tag, auto masked_tag) {
+  // One pipeline step for half hh.  On entry s_cur holds S^T of half hh (masked, relative to the
+  // running max).  Phase 1: the matrix pipe forms S^T of half hh+1 into s_next; phase 2: it
+  // accumulates O^T += V^T P^T of half hh.  TILE_START steps (even hh) first synchronise the
+  // workgroup and refill the ring; MASKED selects the rare variant for halves hh+1 that reach past
+  // the causal horizon (mask, then row max, after the matrix work); CLAMP the variant whose DMA
+  // may run past the end of the cache.
+  auto step = [&](floatx16 (&s_cur)[QB], floatx16 (&s_next)[QB], int hh, auto tile_start_tag, auto masked_tag,
+                  auto clamp_tag) __attribute__((always_inline)) {
     constexpr bool TILE_START = decltype(tile_start_tag)::value;
     constexpr bool MASKED = decltype(masked_tag)::value;
     const int t = hh >> 1;
+    constexpr int KIMM = TILE_START ? HALFB : 0;  // even hh: half hh+1 is the second half of tile t
+    constexpr int VIMM = TILE_START ? 0 : HALFB;  // even hh: half hh is the first half of tile t
     if (TILE_START) {
       // K[t+1] and V[t] were issued NV-1 tiles ago: they are the oldest group in flight
       wait_vm<(NV - 2) * LPG>();
       __builtin_amdgcn_s_barrier();  // ... for every wavefront; also: everyone is done reading K[t-1], V[t-1]
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vaddr[db] = voff[db] + (unsigned)((NK + t % NV) * TILEB);
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kaddr[ks] = koff[ks] + (unsigned)(((t + 1) % NK) * TILEB);
     }
     bf16x2 ones;
     ones[0] = (__bf16)1.0f;
     ones[1] = (__bf16)1.0f;
-    float m_use[QB], lsum[QB];
+    float lsum[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      m_use[qb] = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
-      lsum[qb] = 0.f;
-    }
-    bf16x8 pb[QB][2];
-    // pairs [k0, k1): P = 2^(S*sc - m) rounded to bf16, row sums of the rounded values
-    auto softmax_pairs = [&](int k0, int k1) {
+    for (int qb = 0; qb < QB; ++qb) lsum[qb] = 0.f;
+    uintx4 pb[QB][2];  // P^T fragments: 8 bf16 per 16-key slab, as packed pairs
+    // pairs [k0, k1): P = 2^(S') rounded to bf16, row sums of the rounded values.  The empty asm
+    // statements pin each result where it is computed (behind its MFMA) instead of letting the
+    // optimiser sink the work to the first use.
+    auto softmax_pairs = [&](int k0, int k1) __attribute__((always_inline)) {
 #pragma unroll
       for (int k = k0; k < k1; ++k) {
         const int slab = k / (QB * 4), kk = k % (QB * 4);
-        const int qb = kk >> 2, j = 2 * (kk & 3), r = 8 * slab + j;
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[qb][r], sc, -m_use[qb]));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[qb][r + 1], sc, -m_use[qb]));
+        const int qb = kk >> 2, j = kk & 3, r = 8 * slab + 2 * j;
         bf16x2 pk;
-        pk[0] = (__bf16)p0;
-        pk[1] = (__bf16)p1;
+        pk[0] = (__bf16)__builtin_amdgcn_exp2f(s_cur[qb][r]);
+        pk[1] = (__bf16)__builtin_amdgcn_exp2f(s_cur[qb][r + 1]);
         lsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lsum[qb], false);
-        pb[qb][slab][j] = pk[0];
-        pb[qb][slab][j + 1] = pk[1];
+        unsigned pku = __builtin_bit_cast(unsigned, pk);
+        asm volatile("" : "+v"(pku), "+v"(lsum[qb]));
+        pb[qb][slab][j] = pku;
       }
     };
     // ---- phase 1
-    bf16x8 ka[2];
-    ka[0] = k_frag(hh + 1, 0);
+    bf16x8 ka[PF + 1];
+#pragma unroll
+    for (int i = 0; i < PF && i < NS1; ++i) ka[i] = k_frag(i, KIMM);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < NS1; ++ks) {
-      if (ks + 1 < NS1) ka[(ks + 1) & 1] = k_frag(hh + 1, ks + 1);
+      if (ks + PF < NS1) ka[(ks + PF) % (PF + 1)] = k_frag(ks + PF, KIMM);
       if (TILE_START) {  // refill the slots the barrier has just freed: K[t-1]'s and V[t-1]'s
-        if (ks < SLABS) issue_slab(kbase, dma_kc, t + NV, ks, lds0 + (unsigned)(((t + NV) % NK) * TILEB));
-        else issue_slab(vbase, dma_vc, t + NV - 1, ks - SLABS, lds0 + (unsigned)((NK + (t + NV - 1) % NV) * TILEB));
+        if (ks < SLABS) issue_slab(false, t + NV, ks, clamp_tag);
+        else issue_slab(true, t + NV - 1, ks - SLABS, clamp_tag);
       }
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         const int i = ks * QB + qb;  // MFMA index within phase 1
         if (ks == 0)
-          mfma_qk_first(s_next[qb], ka[ks & 1], qf[qb][ks]);
+          mfma_qk_first(s_next[qb], ka[ks % (PF + 1)], qf[qb][ks], negm[qb]);
         else
-          mfma_qk(s_next[qb], ka[ks & 1], qf[qb][ks]);
+          mfma_qk(s_next[qb], ka[ks % (PF + 1)], qf[qb][ks]);
         __builtin_amdgcn_sched_barrier(0);
         softmax_pairs((i * P1) / M1, ((i + 1) * P1) / M1);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     // ---- phase 2
-    float mx[QB];
-    bf16x8 va[2];
-    va[0] = v_frag(hh, 0, 0);
+    float mx[QB], dm[QB];
+    bool need_rescale = false;
+    bf16x8 va[PF + 1];
+#pragma unroll
+    for (int i = 0; i < PF && i < NS2; ++i) va[i] = v_frag(i / DB, i % DB, VIMM);
     asm volatile("s_nop 1" ::: "memory");  // vector-ALU results (P) settle before the matrix pipe reads them
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int sl = 0; sl < NS2; ++sl) {
       const int tt = sl / DB, db = sl % DB;
-      if (sl + 1 < NS2) va[(sl + 1) & 1] = v_frag(hh, (sl + 1) / DB, (sl + 1) % DB);
+      if (sl + PF < NS2) va[(sl + PF) % (PF + 1)] = v_frag((sl + PF) / DB, (sl + PF) % DB, VIMM);
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         const int i = sl * QB + qb;  // MFMA index within phase 2
-        mfma_pv(o[qb][db], va[sl & 1], pb[qb][tt]);
+        mfma_pv(o[qb][db], va[sl % (PF + 1)], __builtin_bit_cast(bf16x8, pb[qb][tt]));
         __builtin_amdgcn_sched_barrier(0);
-        if (i < H2) {
-          softmax_pairs(P1 + (i * (NP - P1)) / H2, P1 + ((i + 1) * (NP - P1)) / H2);
-        } else if (!MASKED) {
-          // row maxima of s_next: its MFMAs were issued at least H2 MFMAs ago
+        if (i < H2) softmax_pairs(P1 + (i * (NP - P1)) / H2, P1 + ((i + 1) * (NP - P1)) / H2);
+        if (!MASKED) {
+          // row maxima of s_next (its last MFMA is at least RM0 MFMAs old), then the rescale decision
+          if (i >= RM0 && i < RM1) {
 #pragma unroll
-          for (int k = ((i - H2) * NP) / H2; k < ((i - H2 + 1) * NP) / H2; ++k) {
-            const int q2 = k >> 3, r = 2 * (k & 7);
-            if (r == 0)
-              mx[q2] = fmaxf(s_next[q2][0], s_next[q2][1]);
-            else
-              mx[q2] = fmaxf(fmaxf(mx[q2], s_next[q2][r]), s_next[q2][r + 1]);
+            for (int k = ((i - RM0) * NP) / (RM1 - RM0); k < ((i - RM0 + 1) * NP) / (RM1 - RM0); ++k) {
+              const int q2 = k >> 3, r = 2 * (k & 7);
+              if (r == 0)
+                mx[q2] = fmaxf(s_next[q2][0], s_next[q2][1]);
+              else
+                mx[q2] = fmaxf(fmaxf(mx[q2], s_next[q2][r]), s_next[q2][r + 1]);
+              asm volatile("" : "+v"(mx[q2]));
+            }
           }
+          if (i == RM1) need_rescale = rescale_decide(mx, dm);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -374,8 +452,13 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       for (int qb = 0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
       mask_half(s_next, hh + 1);
       rowmax_all(s_next, mx);
+      need_rescale = rescale_decide(mx, dm);
     }
-    rescale(mx);
+    if (__builtin_expect(need_rescale, 0)) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
+      rescale_apply(dm, s_next);
+    }
   };
 
   if (t_begin < t_end) {
@@ -388,14 +471,16 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     }
     wait_vm<(NV - 1) * LPG>();
     __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kaddr[ks] = koff[ks] + (unsigned)((t_begin % NK) * TILEB);
     {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a = k_frag(2 * t_begin, ks);
+        const bf16x8 a = k_frag(ks, 0);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
           if (ks == 0)
-            mfma_qk_first(sA[qb], a, qf[qb][ks]);
+            mfma_qk_first(sA[qb], a, qf[qb][ks], negm[qb]);
           else
             mfma_qk(sA[qb], a, qf[qb][ks]);
         }
@@ -403,23 +488,30 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) mfma_settle_v(sA[qb]);
       if (t_begin * BN + 32 > vis_min) mask_half(sA, 2 * t_begin);
-      float mx[QB];
+      float mx[QB], dm[QB];
       rowmax_all(sA, mx);
-      rescale(mx);
+      if (rescale_decide(mx, dm)) rescale_apply(dm, sA);
     }
     // Tiles whose two steps only produce halves entirely below the nearest causal horizon take the
     // fast variant: step 2t+1 produces half 2t+2 = keys [64t+64, 64t+96), so it needs 64t+96 <= vis_min.
     int t_fast = (vis_min - 96) / BN + 1;  // first tile that is not fast (vis_min >= 1)
     if (vis_min < 96) t_fast = 0;
     if (t_fast > t_end) t_fast = t_end;
+    // ... and tiles whose refill (tile t + NV) lies entirely inside the cache need no row clamp
+    int t_nc = (Lm1 + 1) / BN - NV;
+    if (t_nc > t_fast) t_nc = t_fast;
     int t = t_begin;
+    for (; t < t_nc; ++t) {
+      step(sA, sB, 2 * t, std::true_type{}, std::false_type{}, std::false_type{});
+      step(sB, sA, 2 * t + 1, std::false_type{}, std::false_type{}, std::false_type{});
+    }
     for (; t < t_fast; ++t) {
-      step(sA, sB, 2 * t, std::true_type{}, std::false_type{});
-      step(sB, sA, 2 * t + 1, std::false_type{}, std::false_type{});
+      step(sA, sB, 2 * t, std::true_type{}, std::false_type{}, std::true_type{});
+      step(sB, sA, 2 * t + 1, std::false_type{}, std::false_type{}, std::true_type{});
     }
     for (; t < t_end; ++t) {
-      step(sA, sB, 2 * t, std::true_type{}, std::true_type{});
-      step(sB, sA, 2 * t + 1, std::false_type{}, std::true_type{});
+      step(sA, sB, 2 * t, std::true_type{}, std::true_type{}, std::true_type{});
+      step(sB, sA, 2 * t + 1, std::false_type{}, std::true_type{}, std::true_type{});
     }
     wait_vm<0>();  // nothing of ours may still be writing LDS when the workgroup retires
 #pragma unroll
@@ -482,7 +574,7 @@ static hipError_t launch_one(const AttnParams& p, hipStream_t s) {
 }
 
 hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, int qb, hipStream_t s) {
-  if (head_dim == 128) return qb == 2 ? launch_one<128, 2, 3>(p, s) : launch_one<128, 1, 2>(p, s);
+  if (head_dim == 128) return qb == 2 ? launch_one<128, 2, KVFOLD_NV2>(p, s) : launch_one<128, 1, 2>(p, s);
   if (head_dim == 64) return qb == 2 ? launch_one<64, 2, 3>(p, s) : launch_one<64, 1, 2>(p, s);
   return hipErrorInvalidValue;
 }

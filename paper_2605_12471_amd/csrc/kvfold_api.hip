@@ -62,6 +62,8 @@ int validate_config(const kvfold_config_t* c) {
   // sizes the kernels index with 32-bit row counts / 64-bit byte offsets
   if (c->capacity_tokens > (int64_t)1 << 30 || (int64_t)c->chunk_tokens * c->n_q_heads > (int64_t)1 << 28)
     return KVFOLD_ERR_UNSUPPORTED;
+  // the attention kernels address one KV head's rows with 32-bit byte offsets
+  if (c->capacity_tokens * c->head_dim * elem_size(c->dtype) > (int64_t)0xFFFFFFFFll) return KVFOLD_ERR_UNSUPPORTED;
   if (c->chunk_tokens > c->capacity_tokens) return KVFOLD_ERR_INVALID_ARG;
   return KVFOLD_OK;
 }
