@@ -65,6 +65,12 @@ __device__ __forceinline__ void dma16(const unsigned char* base_uniform, unsigne
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base_uniform), "s"(lds_base_uniform)
                : "memory");
 }
+// Wait until at most N LDS reads are outstanding (compiler-visible, so that it adds none of its own
+// for fragments covered by this wait).  gfx9 encoding: vmcnt and expcnt left at their maxima.
+template <int N>
+__device__ __forceinline__ void wait_lds() {
+  __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8));
+}
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -92,9 +98,6 @@ __device__ __forceinline__ void mfma_settle_a(floatx16& x) {
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(x));
 }
 
-#ifndef KVFOLD_LDS_PF
-#define KVFOLD_LDS_PF 1  // LDS fragment reads run this many slots ahead of the MFMAs that use them
-#endif
 #ifndef KVFOLD_P1_EIGHTHS
 #define KVFOLD_P1_EIGHTHS 6  // pairs of phase 1 = QB * this (4..8)
 #endif
@@ -195,10 +198,9 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   const unsigned dma_voff = (unsigned)dma_row0 * ROWB + dma_vc;
   // slab i of tile t of K (is_v = false) or V; CLAMP redirects rows past the cache end to the last
   // valid row (they are masked anyway, but are never read from memory)
-  auto issue_slab = [&](bool is_v, int t, int i, auto clamp_tag) __attribute__((always_inline)) {
+  auto issue_slab = [&](bool is_v, int t, int slot, int i, auto clamp_tag) __attribute__((always_inline)) {
     constexpr bool CLAMP = decltype(clamp_tag)::value;
-    const unsigned slot = is_v ? (unsigned)(NK + t % NV) : (unsigned)(t % NK);
-    const unsigned lds = lds0 + slot * TILEB + (unsigned)((w + 4 * i) * 1024);
+    const unsigned lds = lds0 + (unsigned)(((is_v ? NK : 0) + slot) * TILEB + (w + 4 * i) * 1024);
     unsigned off;
     if (CLAMP) {
       unsigned grow = (unsigned)(t * BN + dma_row0 + i * 4 * RPS);
@@ -211,27 +213,29 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   };
   auto issue_k = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < SLABS; ++i) issue_slab(false, t, i, std::true_type{});
+    for (int i = 0; i < SLABS; ++i) issue_slab(false, t, t % NK, i, std::true_type{});
   };
   auto issue_v = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < SLABS; ++i) issue_slab(true, t, i, std::true_type{});
+    for (int i = 0; i < SLABS; ++i) issue_slab(true, t, t % NV, i, std::true_type{});
   };
 
-  // ---- LDS read offsets (per lane, without the ring slot)
+  // ---- LDS read offsets (per lane) of the tile currently being read, ring slot included; moved
+  // from slot to slot once per tile
   // K fragment (A operand of S^T): row kb*32+m, chunk ks*2+hi, swizzled by row % KSW = m % KSW
-  unsigned koff[KS];
+  int kslot = t_begin % NK, vslot = t_begin % NV;  // ring slots of tile t (wave-uniform)
+  unsigned kaddr[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) koff[ks] = (unsigned)(m * ROWB + (((ks * 2 + hi) ^ (m % KSW)) * 16));
+  for (int ks = 0; ks < KS; ++ks)
+    kaddr[ks] = (unsigned)(m * ROWB + (((ks * 2 + hi) ^ (m % KSW)) * 16)) + (unsigned)(kslot * TILEB);
   // V^T fragment via transpose read: lane i of a 16-lane block supplies row (i/4) of a 4-row group and 4 columns
   const int i16 = l & 15, b2 = (l >> 4) & 1;
   const int v_row = 4 * hi + (i16 >> 2);  // + 16*tt (+8)
-  unsigned voff[DB];
+  unsigned vaddr[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
-    voff[db] = (unsigned)(v_row * ROWB + (((4 * db + 2 * b2 + ((i16 & 3) >> 1)) ^ ((v_row & 3) * VSW)) * 16) + 8 * (i16 & 1));
-  // offsets including the ring slot of the tile currently being read; refreshed once per tile
-  unsigned kaddr[KS], vaddr[DB];
+    vaddr[db] = (unsigned)(v_row * ROWB + (((4 * db + 2 * b2 + ((i16 & 3) >> 1)) ^ ((v_row & 3) * VSW)) * 16) + 8 * (i16 & 1)) +
+                (unsigned)((NK + vslot) * TILEB);
 
   // ---- running state
   floatx16 o[QB][DB];   // O^T accumulators (AGPRs)
@@ -335,15 +339,19 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   static_assert(P1 >= QB * 4 && P1 <= NP, "slab 0 must be complete before phase 2");
   constexpr int RM0 = M2 >= 8 ? 2 : 1, RM1 = M2 - RM0;  // phase-2 MFMA slots that carry the row-max work / the decision
   static_assert(RM1 > RM0 && RM1 < M2, "phase 2 too short");
-  constexpr int PF = KVFOLD_LDS_PF;
+  constexpr int GK = NS1 / 2;  // K fragments fetched from LDS per batch (two batches per phase 1)
+  constexpr int GV = NS2 / 2;  // V^T fragments per batch (two batches per phase 2)
+  static_assert(GK >= 1 && GV >= 1, "batch shape");
 
   floatx16 sA[QB], sB[QB];
+  bf16x8 kg[2][GK], vg[2][GV];  // fragment batches in flight: LDS reads are issued a batch ahead, so
+                                // one wait covers a whole batch
   // One pipeline step for half hh.  On entry s_cur holds S^T of half hh (masked, relative to the
-  // running max).  Phase 1: the matrix pipe forms S^T of half hh+1 into s_next; phase 2: it
-  // accumulates O^T += V^T P^T of half hh.  TILE_START steps (even hh) first synchronise the
-  // workgroup and refill the ring; MASKED selects the rare variant for halves hh+1 that reach past
-  // the causal horizon (mask, then row max, after the matrix work); CLAMP the variant whose DMA
-  // may run past the end of the cache.
+  // running max) and kg[0] the first batch of K fragments of half hh+1.  Phase 1: the matrix pipe
+  // forms S^T of half hh+1 into s_next; phase 2: it accumulates O^T += V^T P^T of half hh.
+  // TILE_START steps (even hh) first synchronise the workgroup and refill the ring; MASKED selects
+  // the rare variant for halves hh+1 that reach past the causal horizon (mask, then row max, after
+  // the matrix work); CLAMP the variant whose DMA may run past the end of the cache.
   auto step = [&](floatx16 (&s_cur)[QB], floatx16 (&s_next)[QB], int hh, auto tile_start_tag, auto masked_tag,
                   auto clamp_tag) __attribute__((always_inline)) {
     constexpr bool TILE_START = decltype(tile_start_tag)::value;
@@ -351,59 +359,70 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     const int t = hh >> 1;
     constexpr int KIMM = TILE_START ? HALFB : 0;  // even hh: half hh+1 is the second half of tile t
     constexpr int VIMM = TILE_START ? 0 : HALFB;  // even hh: half hh is the first half of tile t
+    int kslot_prev = 0, vslot_prev = 0;
     if (TILE_START) {
       // K[t+1] and V[t] were issued NV-1 tiles ago: they are the oldest group in flight
       wait_vm<(NV - 2) * LPG>();
       __builtin_amdgcn_s_barrier();  // ... for every wavefront; also: everyone is done reading K[t-1], V[t-1]
-#pragma unroll
-      for (int db = 0; db < DB; ++db) vaddr[db] = voff[db] + (unsigned)((NK + t % NV) * TILEB);
-    } else {
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kaddr[ks] = koff[ks] + (unsigned)(((t + 1) % NK) * TILEB);
+      kslot_prev = kslot == 0 ? NK - 1 : kslot - 1;  // K[t-1]'s slot receives K[t+NV]
+      vslot_prev = vslot == 0 ? NV - 1 : vslot - 1;  // V[t-1]'s slot receives V[t+NV-1]
     }
-    bf16x2 ones;
-    ones[0] = (__bf16)1.0f;
-    ones[1] = (__bf16)1.0f;
     float lsum[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) lsum[qb] = 0.f;
     uintx4 pb[QB][2];  // P^T fragments: 8 bf16 per 16-key slab, as packed pairs
-    // pairs [k0, k1): P = 2^(S') rounded to bf16, row sums of the rounded values.  The empty asm
-    // statements pin each result where it is computed (behind its MFMA) instead of letting the
-    // optimiser sink the work to the first use.
+    // Pair k: P = 2^(S') for two logits (exp2 x2), pack to bf16 (x1), add to the row sum of the
+    // ROUNDED values (dot2 with (1,1), x1).  The four instructions are issued as one block, with
+    // the dot2 of the PREVIOUS pair placed between the exps and the pack: that gives the
+    // transcendental results the idle cycle they need before they are read, without a no-op.
+    unsigned pk_prev = 0;  // packed pair whose row-sum contribution is still pending (0 adds nothing)
+    int qb_prev = 0;
     auto softmax_pairs = [&](int k0, int k1) __attribute__((always_inline)) {
 #pragma unroll
       for (int k = k0; k < k1; ++k) {
         const int slab = k / (QB * 4), kk = k % (QB * 4);
         const int qb = kk >> 2, j = kk & 3, r = 8 * slab + 2 * j;
-        bf16x2 pk;
-        pk[0] = (__bf16)__builtin_amdgcn_exp2f(s_cur[qb][r]);
-        pk[1] = (__bf16)__builtin_amdgcn_exp2f(s_cur[qb][r + 1]);
-        lsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lsum[qb], false);
-        unsigned pku = __builtin_bit_cast(unsigned, pk);
-        asm volatile("" : "+v"(pku), "+v"(lsum[qb]));
+        float e0, e1;
+        unsigned pku;
+        asm volatile(
+            "v_exp_f32_e32 %0, %5\n\t"
+            "v_exp_f32_e32 %1, %6\n\t"
+            "v_dot2c_f32_bf16_e32 %3, 0x3f803f80, %4\n\t"
+            "v_cvt_pk_bf16_f32 %2, %0, %1"
+            : "=&v"(e0), "=&v"(e1), "=v"(pku), "+v"(lsum[qb_prev])
+            : "v"(pk_prev), "v"(s_cur[qb][r]), "v"(s_cur[qb][r + 1]));
         pb[qb][slab][j] = pku;
+        pk_prev = pku;
+        qb_prev = qb;
       }
     };
+    auto sum_last_pair = [&]() __attribute__((always_inline)) {
+      asm volatile("v_dot2c_f32_bf16_e32 %0, 0x3f803f80, %1" : "+v"(lsum[qb_prev]) : "v"(pk_prev));
+    };
     // ---- phase 1
-    bf16x8 ka[PF + 1];
-#pragma unroll
-    for (int i = 0; i < PF && i < NS1; ++i) ka[i] = k_frag(i, KIMM);
-    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < NS1; ++ks) {
-      if (ks + PF < NS1) ka[(ks + PF) % (PF + 1)] = k_frag(ks + PF, KIMM);
-      if (TILE_START) {  // refill the slots the barrier has just freed: K[t-1]'s and V[t-1]'s
-        if (ks < SLABS) issue_slab(false, t + NV, ks, clamp_tag);
-        else issue_slab(true, t + NV - 1, ks - SLABS, clamp_tag);
+      if (ks == 0) {
+#pragma unroll
+        for (int j = 0; j < GK; ++j) kg[1][j] = k_frag(GK + j, KIMM);
+        wait_lds<GK>();  // kg[0] has landed
+      }
+      if (ks == GK) {
+#pragma unroll
+        for (int j = 0; j < GV; ++j) vg[0][j] = v_frag(j / DB, j % DB, VIMM);
+        wait_lds<2 * GV>();  // kg[1] has landed
+      }
+      if (TILE_START) {  // refill the slots the barrier has just freed
+        if (ks < SLABS) issue_slab(false, t + NV, kslot_prev, ks, clamp_tag);
+        else issue_slab(true, t + NV - 1, vslot_prev, ks - SLABS, clamp_tag);
       }
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         const int i = ks * QB + qb;  // MFMA index within phase 1
         if (ks == 0)
-          mfma_qk_first(s_next[qb], ka[ks % (PF + 1)], qf[qb][ks], negm[qb]);
+          mfma_qk_first(s_next[qb], kg[ks / GK][ks % GK], qf[qb][ks], negm[qb]);
         else
-          mfma_qk(s_next[qb], ka[ks % (PF + 1)], qf[qb][ks]);
+          mfma_qk(s_next[qb], kg[ks / GK][ks % GK], qf[qb][ks]);
         __builtin_amdgcn_sched_barrier(0);
         softmax_pairs((i * P1) / M1, ((i + 1) * P1) / M1);
         __builtin_amdgcn_sched_barrier(0);
@@ -412,21 +431,43 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     // ---- phase 2
     float mx[QB], dm[QB];
     bool need_rescale = false;
-    bf16x8 va[PF + 1];
-#pragma unroll
-    for (int i = 0; i < PF && i < NS2; ++i) va[i] = v_frag(i / DB, i % DB, VIMM);
     asm volatile("s_nop 1" ::: "memory");  // vector-ALU results (P) settle before the matrix pipe reads them
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int sl = 0; sl < NS2; ++sl) {
       const int tt = sl / DB, db = sl % DB;
-      if (sl + PF < NS2) va[(sl + PF) % (PF + 1)] = v_frag((sl + PF) / DB, (sl + PF) % DB, VIMM);
+      if (sl == 0) {
+#pragma unroll
+        for (int j = 0; j < GV; ++j) vg[1][j] = v_frag((GV + j) / DB, (GV + j) % DB, VIMM);
+        wait_lds<2 * GV>();  // vg[0] has landed
+      }
+      if (sl == GV) {
+        // first K batch of the NEXT step (half hh+2); after an even step that is a new tile, whose
+        // V tile is also the one the next even step will read
+        if (TILE_START) {
+          const int kn = kslot + 1 == NK ? 0 : kslot + 1;
+          const unsigned dk = (unsigned)((kn - kslot) * TILEB);
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) kaddr[ks] += dk;
+          kslot = kn;
+        } else {
+          const int vn = vslot + 1 == NV ? 0 : vslot + 1;
+          const unsigned dv = (unsigned)((vn - vslot) * TILEB);
+#pragma unroll
+          for (int d2 = 0; d2 < DB; ++d2) vaddr[d2] += dv;
+          vslot = vn;
+        }
+#pragma unroll
+        for (int j = 0; j < GK; ++j) kg[0][j] = k_frag(j, TILE_START ? 0 : HALFB);
+        wait_lds<GK>();  // vg[1] has landed
+      }
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         const int i = sl * QB + qb;  // MFMA index within phase 2
-        mfma_pv(o[qb][db], va[sl % (PF + 1)], __builtin_bit_cast(bf16x8, pb[qb][tt]));
+        mfma_pv(o[qb][db], vg[sl / GV][sl % GV], __builtin_bit_cast(bf16x8, pb[qb][tt]));
         __builtin_amdgcn_sched_barrier(0);
         if (i < H2) softmax_pairs(P1 + (i * (NP - P1)) / H2, P1 + ((i + 1) * (NP - P1)) / H2);
+        if (i == H2 - 1) sum_last_pair();  // last pending row-sum contribution
         if (!MASKED) {
           // row maxima of s_next (its last MFMA is at least RM0 MFMAs old), then the rescale decision
           if (i >= RM0 && i < RM1) {
@@ -471,8 +512,6 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     }
     wait_vm<(NV - 1) * LPG>();
     __builtin_amdgcn_s_barrier();
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) kaddr[ks] = koff[ks] + (unsigned)((t_begin % NK) * TILEB);
     {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -491,6 +530,9 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       float mx[QB], dm[QB];
       rowmax_all(sA, mx);
       if (rescale_decide(mx, dm)) rescale_apply(dm, sA);
+      // first K batch of the first step: second half of tile t_begin
+#pragma unroll
+      for (int j = 0; j < GK; ++j) kg[0][j] = k_frag(j, HALFB);
     }
     // Tiles whose two steps only produce halves entirely below the nearest causal horizon take the
     // fast variant: step 2t+1 produces half 2t+2 = keys [64t+64, 64t+96), so it needs 64t+96 <= vis_min.
