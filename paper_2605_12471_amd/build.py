@@ -15,7 +15,10 @@ HIPCC_FLAGS = [
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    # the compiler's per-kernel register / scratch report is kept next to the library
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+RESOURCE_REPORT = os.path.join(LIB_DIR, "kernel_resources.txt")
 
 
 def build_library(verbose: bool = False) -> str:
@@ -29,13 +32,19 @@ def build_library(verbose: bool = False) -> str:
         objs.append(obj)
         cmd = [hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    report = []
     for cmd, p in procs:
         out, _ = p.communicate()
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+        lines = [l for l in out.splitlines() if "packed-fp32-ops" not in l]
         if p.returncode:
-            raise RuntimeError("hipcc failed: %s\n%s" % (" ".join(cmd), out))
-        if verbose and out.strip():
-            print(out)
+            raise RuntimeError("hipcc failed: %s\n%s" % (" ".join(cmd), "\n".join(lines)))
+        report += [l.split("remark: ", 1)[1].replace(" [-Rpass-analysis=kernel-resource-usage]", "")
+                   for l in lines if "remark: " in l and "kernel-resource-usage" in l]
+        rest = "\n".join(l for l in lines if "kernel-resource-usage" not in l and "|" not in l[:12])
+        if verbose and rest.strip():
+            print(rest)
+    with open(RESOURCE_REPORT, "w") as f:
+        f.write("\n".join(report) + "\n")
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
     subprocess.run(cmd, check=True)
     return LIB_PATH

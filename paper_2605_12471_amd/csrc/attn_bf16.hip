@@ -295,7 +295,9 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       const float cur = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
-      const float m2 = fmaxf(m_run[qb], cur + dm[qb]);
+      // only rows that asked for it move, so a row's arithmetic never depends on its wave neighbours
+      const bool mine = (dm[qb] > kRescaleThreshold) || (m_run[qb] == -INFINITY && dm[qb] > -INFINITY);
+      const float m2 = mine ? fmaxf(m_run[qb], cur + dm[qb]) : m_run[qb];
       const float use = (m2 == -INFINITY) ? 0.f : m2;
       const float delta = use - cur;
       const float alpha = __builtin_amdgcn_exp2f(-delta);

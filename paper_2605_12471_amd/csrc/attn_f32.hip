@@ -141,7 +141,8 @@ __global__ void __launch_bounds__(256, 1) attn_f32_kernel(AttnParams p) {
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
     mx = pair_max_f(mx) * sc;
     if (__any(mx > m_run + kThresh)) {
-      const float m2 = fmaxf(m_run, mx);
+      // only rows that asked for it move, so a row's arithmetic never depends on its wave neighbours
+      const float m2 = (mx > m_run + kThresh) ? mx : m_run;
       const float alpha = (m2 == -INFINITY) ? 1.f : exp2f(m_run - m2);
       m_run = m2;
       l_run *= alpha;

@@ -1,0 +1,136 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares, and
+every error path that can be decided without a GPU returns the documented status."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_12471_amd as kv
+from paper_2605_12471_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(kv.lib_path()):
+        build.build_library()
+    return kv.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "kvfold.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvfold_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"kvfold_cache_create", "kvfold_step", "kvfold_step_ex", "kvfold_cache_destroy"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in kvfold.h but not exported"
+
+
+def test_python_binding_has_the_same_names():
+    for n in _declared_functions():
+        assert hasattr(kv, n), f"binding lacks {n}"
+
+
+def test_struct_layout_matches_header():
+    # field order and natural alignment of kvfold_config_t (64-bit ABI)
+    c = binding.kvfold_config_t
+    assert ctypes.sizeof(c) == 64
+    assert c.capacity_tokens.offset == 24 and c.kv_buffer.offset == 48 and c.kv_buffer_bytes.offset == 56
+
+
+def test_bytes_required_matches_paper_accounting(lib):
+    """Tab. 4 caption: 32 layers x 8 KV heads x 128 dims x (K,V) x 2 bytes = 131,072 bytes per token."""
+    vals = {}
+    rows = []
+    for line in open(os.path.join(ROOT, "tests", "golden", "paper_cache_accounting.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        parts = line.split()
+        if parts[0] == "kv_gb":
+            rows.append((int(parts[1]), float(parts[2])))
+        elif len(parts) == 2:
+            vals[parts[0]] = int(parts[1])
+    cfg = binding.make_config(vals["layers"], 32, vals["kv_heads"], vals["head_dim"], 1, 1, kv.KVFOLD_BF16)
+    assert kv.kvfold_cache_bytes_required(cfg) == vals["bytes_per_token"]
+    for tokens, gb in rows:
+        cfg.capacity_tokens = tokens
+        need = kv.kvfold_cache_bytes_required(cfg)
+        assert need == tokens * vals["bytes_per_token"]
+        assert abs(need / 1e9 - gb) < 0.006          # the table prints two decimals
+    cfg.capacity_tokens = 131072
+    assert kv.kvfold_cache_bytes_required(cfg) == 17179869184   # 16 GiB exactly
+    # fp32 doubles it
+    cfg.dtype = kv.KVFOLD_F32
+    assert kv.kvfold_cache_bytes_required(cfg) == 2 * 17179869184
+
+
+@pytest.mark.parametrize("mutate,status", [
+    (lambda c: setattr(c, "struct_size", 8), -1),
+    (lambda c: setattr(c, "n_layers", 0), -1),
+    (lambda c: setattr(c, "chunk_tokens", 0), -1),
+    (lambda c: setattr(c, "capacity_tokens", 0), -1),
+    (lambda c: setattr(c, "device", -1), -1),
+    (lambda c: setattr(c, "softmax_scale", -1.0), -1),
+    (lambda c: setattr(c, "softmax_scale", float("nan")), -1),
+    (lambda c: setattr(c, "chunk_tokens", 4096), -1),           # chunk larger than capacity
+    (lambda c: setattr(c, "kv_buffer", 0x1001), -1),            # misaligned caller buffer
+    (lambda c: setattr(c, "head_dim", 96), -5),
+    (lambda c: setattr(c, "n_q_heads", 7), -5),                 # not a multiple of Hkv
+    (lambda c: setattr(c, "dtype", 7), -5),
+    (lambda c: setattr(c, "capacity_tokens", 1 << 31), -5),
+])
+def test_create_rejects_bad_config_before_touching_the_gpu(lib, mutate, status):
+    cfg = binding.make_config(2, 8, 2, 128, 64, 1024, kv.KVFOLD_BF16)
+    mutate(cfg)
+    rc, h = kv.kvfold_cache_create(cfg)
+    assert rc == status and h is None
+    assert kv.kvfold_cache_bytes_required(cfg) == 0
+
+
+def test_caller_buffer_too_small_is_oom(lib):
+    cfg = binding.make_config(1, 8, 2, 128, 64, 1024, kv.KVFOLD_BF16, kv_buffer=0x10000, kv_buffer_bytes=1024)
+    rc, h = kv.kvfold_cache_create(cfg)
+    assert rc == -6 and h is None
+
+
+def test_null_handles(lib):
+    assert lib.kvfold_cache_create(None, None) == -1
+    assert kv.kvfold_cache_destroy(None) == 0                     # NULL is a no-op
+    assert kv.kvfold_cache_length(None, 0) == -1
+    assert kv.kvfold_step(None, 0, 1, 1, 1, 0, 1, 0) == -1
+    assert kv.kvfold_step_ex(None, 0, 1, 1, 1, 1, 0, 1, None, 0) == -1
+    assert kv.kvfold_cache_set_length(None, 0, 0) == -1
+    assert kv.kvfold_cache_set_tuning(None, 0, 0) == -1
+    assert kv.kvfold_cache_plan(None, 1, 1)[0] == -1
+    assert kv.kvfold_cache_view(None, 0)[0] == -1
+    assert kv.kvfold_cache_profile_begin(None, 1) == -1
+    assert kv.kvfold_cache_profile_end(None)[0] == -1
+
+
+def test_status_strings(lib):
+    seen = {kv.kvfold_status_string(s) for s in range(0, -8, -1)}
+    assert len(seen) == 8 and "unknown status" not in seen
+    assert kv.kvfold_status_string(-99) == "unknown status"
+
+
+def test_kernels_use_no_scratch_memory():
+    """Register-resident kernels: the compiler's resource report must show no scratch and no spills."""
+    if not os.path.exists(build.RESOURCE_REPORT):
+        build.build_library()
+    text = open(build.RESOURCE_REPORT).read()
+    blocks = text.split("Function Name: ")[1:]
+    names = [b.splitlines()[0] for b in blocks]
+    assert any("attn_bf16_kernel" in n for n in names) and any("attn_f32_kernel" in n for n in names)
+    for b in blocks:
+        name = b.splitlines()[0]
+        scratch = int(re.search(r"ScratchSize \[bytes/lane\]: (\d+)", b).group(1))
+        spill = int(re.search(r"VGPRs Spill: (\d+)", b).group(1))
+        assert scratch == 0 and spill == 0, f"{name}: scratch {scratch} B/lane, {spill} spilled VGPRs"
+        if "attn_bf16_kernelILi128ELi2" in name:   # the flagship kernel: one wave per SIMD, O and Q in AGPRs
+            assert int(re.search(r"AGPRs: (\d+)", b).group(1)) == 192

@@ -1,0 +1,243 @@
+"""Properties of the HIP fold step that hold at any size, plus the error paths that need a live cache."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_12471_amd as kv
+from paper_2605_12471_amd import binding
+from paper_2605_12471_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import fold_harness
+    return fold_harness
+
+
+def _fold(H, cfg, chunks, mutate=None, sync_each=True, tuning=None):
+    """Run a fold; returns list of per-step outputs (CPU tensors) and the GpuFold (caller closes)."""
+    gpu = H.GpuFold(cfg, capacity=sum(chunks), chunk_tokens=max(chunks))
+    for k_, v_ in (tuning or {}).items():
+        gpu.cache.set_tuning(k_, v_)
+    outs, pos = [], 0
+    for step, C in enumerate(chunks):
+        q, k, v = I.chunk_qkv(cfg, 0, step, n_tokens=C, token_base=pos)
+        if mutate:
+            q, k, v = mutate(step, pos, q, k, v)
+        out = gpu.step(0, q, k, v)
+        if sync_each:
+            torch.cuda.synchronize()
+        outs.append(out)
+        pos += C
+    torch.cuda.synchronize()
+    return [o.cpu() for o in outs], gpu
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_gqa_group_isolation(H, dtype):
+    """Changing the V rows of one KV head changes exactly its G query heads, nothing else (bit for bit)."""
+    cfg = I.FoldConfig("gqa", 20, 1, 12, 3, 128, 96, 0, dtype)
+    chunks = [96, 96, 40]
+    base, g0 = _fold(H, cfg, chunks); g0.close()
+
+    def bump(step, pos, q, k, v):
+        v = v.clone(); v[:, 1] += 1.0
+        return q, k, v
+    pert, g1 = _fold(H, cfg, chunks, mutate=bump); g1.close()
+    for b, p_ in zip(base, pert):
+        same = [h for h in range(12) if torch.equal(b[:, h], p_[:, h])]
+        assert same == [0, 1, 2, 3, 8, 9, 10, 11]
+        # weights sum to one, so the bumped heads move by the bump (up to rounding)
+        assert (p_[:, 4:8].double() - b[:, 4:8].double() - 1.0).abs().max() < (3e-2 if dtype == "bf16" else 1e-5)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_no_causal_leak(H, dtype):
+    """Perturbing key/value row j leaves every output row at a position < j unchanged bit for bit."""
+    cfg = I.FoldConfig("leak", 21, 1, 8, 2, 128, 128, 0, dtype)
+    chunks = [128, 128, 128]
+    base, g0 = _fold(H, cfg, chunks); g0.close()
+    j = 128 + 77   # inside chunk 1
+
+    def poke(step, pos, q, k, v):
+        if pos <= j < pos + k.shape[0]:
+            k, v = k.clone(), v.clone()
+            k[j - pos] *= -3.0
+            v[j - pos] += 5.0
+        return q, k, v
+    pert, g1 = _fold(H, cfg, chunks, mutate=poke); g1.close()
+    b, p_ = torch.cat(base), torch.cat(pert)
+    assert torch.equal(b[:j], p_[:j])
+    assert not torch.equal(b[j:], p_[j:])
+    assert (b[j:].double() - p_[j:].double()).abs().flatten(1).max(1).values.min() > 0   # every later row moved
+
+
+def test_determinism_and_stream_order(H):
+    """Same inputs give bit-identical outputs; steps enqueued back to back without host syncs equal synced steps."""
+    cfg = I.FoldConfig("det", 22, 1, 32, 8, 128, 256, 0, "bf16")
+    chunks = [256] * 6
+    a, g0 = _fold(H, cfg, chunks, sync_each=True); g0.close()
+    b, g1 = _fold(H, cfg, chunks, sync_each=False); g1.close()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    # on a side stream as well
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        c, g2 = _fold(H, cfg, chunks, sync_each=False)
+    g2.close()
+    for x, y in zip(a, c):
+        assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("splits,upw", [(1, 1), (1, 2), (3, 1), (4, 2), (7, 1)])
+def test_launch_shape_does_not_change_results_much(H, oracle, splits, upw):
+    """Different launch geometries (prefix splits, rows per wave) all match the oracle."""
+    cfg = I.FoldConfig("geom", 23, 1, 32, 8, 128, 192, 0, "bf16")
+    chunks = [192] * 8
+    outs, gpu = _fold(H, cfg, chunks, tuning={kv.TUNE_SPLITS: splits, kv.TUNE_UNITS_PER_WAVE: upw})
+    oc = H.make_oracle(oracle, cfg, capacity=sum(chunks))
+    pos = 0
+    try:
+        for step, C in enumerate(chunks):
+            q, k, v = I.chunk_qkv(cfg, 0, step, n_tokens=C, token_base=pos)
+            ref, _ = H.oracle_step(oc, q, k, v, rows=[0, 1, 31, 32, 95, 190, 191])
+            got = H.wide(outs[step])[[0, 1, 31, 32, 95, 190, 191]]
+            assert np.abs(got - ref).max() <= 2e-2
+            pos += C
+    finally:
+        gpu.close()
+
+
+def test_resume_from_copied_rows(H):
+    """The cache rows are the whole recurrent state: copy rows [0, len) into a fresh cache, set its length, go on."""
+    cfg = I.FoldConfig("resume", 24, 1, 8, 2, 128, 64, 0, "bf16")
+    chunks = [64] * 8
+    full, g0 = _fold(H, cfg, chunks); g0.close()
+    first, g1 = _fold(H, cfg, chunks[:4])
+    g2 = H.GpuFold(cfg, capacity=sum(chunks), chunk_tokens=64)
+    try:
+        k1, v1 = g1.cache.view(0)
+        k2, v2 = g2.cache.view(0)
+        n = 4 * 64
+        k2[:, :n].copy_(k1[:, :n]); v2[:, :n].copy_(v1[:, :n])
+        torch.cuda.synchronize()
+        g2.cache.set_length(0, n)
+        for step in range(4, 8):
+            q, k, v = I.chunk_qkv(cfg, 0, step, n_tokens=64, token_base=step * 64)
+            out = g2.step(0, q, k, v).cpu()
+            assert torch.equal(out, full[step])
+    finally:
+        g1.close(); g2.close()
+
+
+def test_rewind_and_reappend(H):
+    """set_length shrinks the host-side length; re-running the step re-appends identical rows."""
+    cfg = I.FoldConfig("rewind", 25, 1, 8, 2, 128, 64, 0, "bf16")
+    outs, gpu = _fold(H, cfg, [64] * 4)
+    try:
+        gpu.cache.set_length(0, 128)
+        for step in (2, 3):
+            q, k, v = I.chunk_qkv(cfg, 0, step, n_tokens=64, token_base=step * 64)
+            assert torch.equal(gpu.step(0, q, k, v).cpu(), outs[step])
+    finally:
+        gpu.close()
+
+
+def test_errors_leave_the_cache_untouched(H):
+    cfg = I.FoldConfig("err", 26, 2, 8, 2, 128, 64, 0, "bf16")
+    gpu = H.GpuFold(cfg, capacity=128, chunk_tokens=64)
+    dev = gpu.dev
+    try:
+        q, k, v = (t.to(dev) for t in I.chunk_qkv(cfg, 0, 0))
+        out = torch.empty_like(q)
+        h = gpu.cache.handle
+        args = (q.data_ptr(), k.data_ptr(), v.data_ptr())
+        assert kv.kvfold_step(h, 2, *args, 0, out.data_ptr(), 0) == -2          # bad layer
+        assert kv.kvfold_step(h, -1, *args, 0, out.data_ptr(), 0) == -2
+        assert kv.kvfold_step(h, 0, *args, 5, out.data_ptr(), 0) == -3          # position does not continue
+        assert kv.kvfold_step(h, 0, None, k.data_ptr(), v.data_ptr(), 0, out.data_ptr(), 0) == -1
+        assert kv.kvfold_step(h, 0, q.data_ptr() + 2, k.data_ptr(), v.data_ptr(), 0, out.data_ptr(), 0) == -1  # misaligned
+        assert kv.kvfold_step_ex(h, 0, *args, 0, 0, out.data_ptr(), None, 0) == -1   # n_tokens = 0
+        assert kv.kvfold_step_ex(h, 0, *args, 65, 0, out.data_ptr(), None, 0) == -1  # n_tokens > chunk_tokens
+        assert kv.kvfold_cache_length(h, 0) == 0
+        assert kv.kvfold_step(h, 0, *args, 0, out.data_ptr(), 0) == 0
+        assert kv.kvfold_step(h, 0, *args, 64, out.data_ptr(), 0) == 0
+        torch.cuda.synchronize()
+        kview, _ = gpu.cache.view(0)
+        before = kview.clone()
+        assert kv.kvfold_step(h, 0, *args, 128, out.data_ptr(), 0) == -4        # capacity exhausted
+        torch.cuda.synchronize()
+        assert kv.kvfold_cache_length(h, 0) == 128 and kv.kvfold_cache_length(h, 1) == 0
+        assert torch.equal(kview, before)
+        assert kv.kvfold_cache_set_length(h, 0, 129) == -4
+        assert kv.kvfold_cache_set_length(h, 3, 0) == -2
+        assert kv.kvfold_cache_set_tuning(h, 99, 0) == -1 and kv.kvfold_cache_set_tuning(h, kv.TUNE_UNITS_PER_WAVE, 3) == -1
+        assert kv.kvfold_cache_plan(h, 0, 64)[0] == -1
+    finally:
+        gpu.close()
+
+
+def test_caller_buffer_with_guard_bands(H, oracle):
+    """A caller-owned K/V buffer is used in place; bytes before and after it are never written."""
+    cfg = I.FoldConfig("guard", 27, 2, 8, 2, 128, 100, 0, "bf16")
+    cap = 300
+    c = binding.make_config(2, 8, 2, 128, 100, cap, kv.KVFOLD_BF16)
+    need = kv.kvfold_cache_bytes_required(c)
+    guard = 4096
+    buf = torch.full((need + 2 * guard,), 0x5A, dtype=torch.uint8, device="cuda:0")
+    base = buf.data_ptr()
+    off = (-base) % 256 + 256
+    c.kv_buffer, c.kv_buffer_bytes = base + off, need
+    rc, h = kv.kvfold_cache_create(c)
+    assert rc == 0
+    try:
+        oc = H.make_oracle(oracle, cfg, capacity=cap)
+        pos = 0
+        for step, C in enumerate([100, 100, 37]):
+            q, k, v = I.chunk_qkv(cfg, 1, step, n_tokens=C, token_base=pos)
+            qd, kd, vd = (t.cuda() for t in (q, k, v))
+            out = torch.empty_like(qd)
+            assert kv.kvfold_step_ex(h, 1, qd.data_ptr(), kd.data_ptr(), vd.data_ptr(), C, pos, out.data_ptr(), None,
+                                     torch.cuda.current_stream().cuda_stream) == 0
+            ref, _ = H.oracle_step(oc, q, k, v)
+            torch.cuda.synchronize()
+            assert np.abs(H.wide(out) - ref).max() <= 2e-2
+            pos += C
+        torch.cuda.synchronize()
+        assert (buf[:off] == 0x5A).all() and (buf[off + need:] == 0x5A).all()
+        # layer 0 was never stepped: its rows are untouched; layer 1 rows past the length too
+        rc, kp, vp, rs, hs = kv.kvfold_cache_view(h, 1)
+        assert rc == 0 and rs == 128 and hs == cap * 128
+        k_off = kp - base
+        layer_bytes = 2 * cap * 128 * 2
+        assert k_off == off + layer_bytes                       # K block: [layer][head][cap][d]
+        assert (buf[off:off + layer_bytes] == 0x5A).all()       # layer 0 K rows
+        kl1 = buf[k_off:k_off + layer_bytes].view(torch.bfloat16).view(2, cap, 128)
+        assert (kl1[:, pos:].view(torch.uint8) == 0x5A).all()   # rows past the length
+        assert np.array_equal(H.bits(kl1[:, :pos]), oc.k_bits[:, :pos])
+    finally:
+        assert kv.kvfold_cache_destroy(h) == 0
+    assert (buf[:off] == 0x5A).all()                            # destroy frees nothing of ours
+
+
+def test_plan_and_profile_api(H):
+    cfg = I.FoldConfig("plan", 28, 1, 32, 8, 128, 256, 0, "bf16")
+    gpu = H.GpuFold(cfg, capacity=8192, chunk_tokens=256)
+    try:
+        wgs, splits = gpu.cache.plan(256, 8192)
+        assert splits > 1 and wgs % splits == 0                # a small chunk on a long prefix is split
+        gpu.cache.set_tuning(kv.TUNE_SPLITS, 1)
+        assert gpu.cache.plan(256, 8192)[1] == 1
+        gpu.cache.set_tuning(kv.TUNE_SPLITS, 0)
+        gpu.cache.profile_begin(4)
+        for step in range(6):
+            q, k, v = I.chunk_qkv(cfg, 0, step)
+            gpu.step(0, q, k, v)
+        n, a, t, m = gpu.cache.profile_end()
+        assert n == 4 and a > 0 and t > 0 and m >= 0
+    finally:
+        gpu.close()
