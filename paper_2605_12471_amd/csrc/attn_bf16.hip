@@ -134,7 +134,15 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   const int g = lid / wgs_per_kvh;
   const int rem = lid - g * wgs_per_kvh;
   const int split = rem / p.wgs_per_head;
-  const int ug = p.wgs_per_head - 1 - (rem - split * p.wgs_per_head);  // heaviest (latest rows) first
+  // Later token blocks see more keys.  Default order: heaviest first (longest-processing-time
+  // first over several rounds of workgroups).  With pair_order the grid is resident at once, two
+  // workgroups per CU, dispatched in id order: the first half descends from the heaviest, the second
+  // half ascends from the lightest, so the two workgroups that share a CU add up to the same work.
+  int ug;
+  {
+    const int idx = rem - split * p.wgs_per_head, W = p.wgs_per_head, half = (W + 1) / 2;
+    ug = (!p.pair_order || idx < half) ? W - 1 - idx : idx - half;
+  }
 
   const int tid = threadIdx.x, l = tid & 63, hi = l >> 5, m = l & 31;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);

@@ -40,7 +40,15 @@ __global__ void __launch_bounds__(256, 1) attn_f32_kernel(AttnParams p) {
   const int g = lid / wgs_per_kvh;
   const int rem = lid - g * wgs_per_kvh;
   const int split = rem / p.wgs_per_head;
-  const int ug = p.wgs_per_head - 1 - (rem - split * p.wgs_per_head);
+  // Later token blocks see more keys.  Default order: heaviest first (longest-processing-time
+  // first over several rounds of workgroups).  With pair_order the grid is resident at once, two
+  // workgroups per CU, dispatched in id order: the first half descends from the heaviest, the second
+  // half ascends from the lightest, so the two workgroups that share a CU add up to the same work.
+  int ug;
+  {
+    const int idx = rem - split * p.wgs_per_head, W = p.wgs_per_head, half = (W + 1) / 2;
+    ug = (!p.pair_order || idx < half) ? W - 1 - idx : idx - half;
+  }
 
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, hi = l >> 5, m = l & 31;
   const int C = p.n_tokens, Hq = p.n_q_heads, G = p.group;

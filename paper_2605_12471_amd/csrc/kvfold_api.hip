@@ -78,7 +78,7 @@ constexpr int kMaxSplits = 32;
 constexpr int kMinTilesPerSplit = 8;
 
 struct Plan {
-  int units_per_wave, units_per_head, wgs_per_head, n_splits, tiles_per_split, n_wgs;
+  int units_per_wave, units_per_head, wgs_per_head, n_splits, tiles_per_split, n_wgs, pair_order;
 };
 
 Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
@@ -87,10 +87,21 @@ Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
   Plan pl;
   pl.units_per_head = G * ((n_tokens + kRowsPerUnit - 1) / kRowsPerUnit);
   int upw = 1;
+  pl.pair_order = 0;
   if (f.dtype == KVFOLD_BF16) {
     upw = c->tune_units_per_wave ? c->tune_units_per_wave : 2;
-    // two units per wave only pays when there are enough units to keep every CU busy
-    if (!c->tune_units_per_wave && (int64_t)f.n_kv_heads * pl.units_per_head < (int64_t)c->n_cu * kUnitsPerWg * 2) upw = 1;
+    const int64_t units = (int64_t)f.n_kv_heads * pl.units_per_head;
+    if (!c->tune_units_per_wave) {
+      // two units per wave only pays when there are enough units to keep every CU busy
+      if (units < (int64_t)c->n_cu * kUnitsPerWg * 2) upw = 1;
+      // Short prefix: the causal part makes late token blocks up to twice as long as early ones.  If
+      // the one-unit-per-wave grid is resident at once (two workgroups per CU) pair heavy with light.
+      const int64_t wgs1 = (int64_t)f.n_kv_heads * ((pl.units_per_head + kUnitsPerWg - 1) / kUnitsPerWg);
+      if (len_after < 7 * (int64_t)n_tokens && wgs1 <= 2 * (int64_t)c->n_cu && wgs1 > (int64_t)c->n_cu) {
+        upw = 1;
+        pl.pair_order = 1;
+      }
+    }
   }
   pl.units_per_wave = upw;
   const int per_wg = kUnitsPerWg * upw;
@@ -115,6 +126,7 @@ Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
   pl.n_splits = (ntiles + pl.tiles_per_split - 1) / pl.tiles_per_split;
   if (pl.n_splits < 1) pl.n_splits = 1;
   pl.n_wgs = (int)(base * pl.n_splits);
+  if (pl.n_splits > 1) pl.pair_order = 0;
   return pl;
 }
 
@@ -269,6 +281,7 @@ int kvfold_step_ex(kvfold_cache_t* c, int layer, const void* q, const void* k_ne
   at.units_per_head = pl.units_per_head;
   at.wgs_per_head = pl.wgs_per_head;
   at.n_wgs = pl.n_wgs;
+  at.pair_order = pl.pair_order;
   at.scale_log2e = c->scale * 1.4426950408889634f;
   if (pl.n_splits > 1 && (int64_t)pl.n_splits * n_tokens * f.n_q_heads > c->ws_rows) return KVFOLD_ERR_HIP;  // planner bug guard
 

@@ -43,6 +43,8 @@ struct AttnParams {
   int32_t units_per_head;  // G * ceil(C / 32)
   int32_t wgs_per_head;    // ceil(units_per_head / units per workgroup)
   int32_t n_wgs;           // Hkv * wgs_per_head * S (the grid is padded to a multiple of 8)
+  int32_t pair_order;      // 1: every workgroup is resident at once, two per CU; order them heaviest-first for the
+                           // first half and lightest-first for the second so each CU gets a balanced pair
   float scale_log2e;       // softmax scale * log2(e)
 };
 
