@@ -288,15 +288,17 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   // by how much the max would grow.  The running max is raised only when it lags by more than
   // 2^16 (or has never been set).  The decision (cross-lane max, compare) is taken early, under
   // the matrix pipe; the branch comes later.
-  auto rescale_decide = [&](const float (&mx)[QB], float (&dm)[QB]) __attribute__((always_inline)) -> bool {
+  auto rescale_need = [&](const float (&dm)[QB]) __attribute__((always_inline)) -> bool {
     int need = 0;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      dm[qb] = pair_max(mx[qb]);
-      // no short-circuit: plain lane-wise compares, one wave-wide reduction at the end
+    for (int qb = 0; qb < QB; ++qb)  // no short-circuit: plain lane-wise compares, one wave-wide reduction at the end
       need |= (int)(dm[qb] > kRescaleThreshold) | ((int)(m_run[qb] == -INFINITY) & (int)(dm[qb] > -INFINITY));
-    }
     return __any(need);
+  };
+  auto rescale_decide = [&](const float (&mx)[QB], float (&dm)[QB]) __attribute__((always_inline)) -> bool {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) dm[qb] = pair_max(mx[qb]);
+    return rescale_need(dm);
   };
   // s holds the logits of the half the maxima came from: they were formed against the old max
   auto rescale_apply = [&](const float (&dm)[QB], floatx16 (&s)[QB]) __attribute__((always_inline)) {
@@ -334,167 +336,172 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     }
   };
 
-  constexpr int NS1 = KS;      // slots of phase 1 (one K fragment, QB MFMAs each); equals LPG
-  constexpr int NS2 = 2 * DB;  // slots of phase 2 (one V^T fragment, QB MFMAs each)
-  static_assert(NS1 == LPG, "one DMA per phase-1 slot");
-  // Vector-ALU work of one step is dealt out behind individual MFMAs so that it hides under the
-  // matrix pipe.  The unit is a pair of logits (2 exp2, 1 pack, 1 dot2).  Pairs are numbered slab 0
-  // first (keys 0..15 of the half, needed by the first half of phase 2), then slab 1 (needed by
-  // the second half of phase 2).
-  constexpr int NP = QB * 8;            // pairs per step
-  constexpr int M1 = NS1 * QB;          // MFMAs of phase 1
-  constexpr int M2 = NS2 * QB;          // MFMAs of phase 2
-  constexpr int H2 = M2 / 2;
-  constexpr int P1 = QB * KVFOLD_P1_EIGHTHS;  // pairs placed in phase 1 (all of slab 0, part of slab 1)
-  static_assert(P1 >= QB * 4 && P1 <= NP, "slab 0 must be complete before phase 2");
-  constexpr int RM0 = M2 >= 8 ? 2 : 1, RM1 = M2 - RM0;  // phase-2 MFMA slots that carry the row-max work / the decision
-  static_assert(RM1 > RM0 && RM1 < M2, "phase 2 too short");
-  constexpr int GK = NS1 / 2;  // K fragments fetched from LDS per batch (two batches per phase 1)
-  constexpr int GV = NS2 / 2;  // V^T fragments per batch (two batches per phase 2)
-  static_assert(GK >= 1 && GV >= 1, "batch shape");
+  // ---- the software pipeline -----------------------------------------------------------------
+  // One step handles one 32-key half hh and consists of M MFMA slots: M1 slots forming S^T of half
+  // hh+1 (phase 1), then M2 slots accumulating O^T += V^T P^T of half hh (phase 2).  A single wave can
+  // hide only a dozen cycles of other instructions under one MFMA and a transcendental costs 16, so
+  // everything else is dealt out evenly, a fixed share behind every MFMA:
+  //   * exp2 / pack / row-sum of half hh in slots [0, EW): one "event" = one exp2 (the second
+  //     event of a logit pair also packs the pair and adds the previous pair to the row sum);
+  //   * LDS fragment reads one batch ahead, one instruction per slot, one wait per batch;
+  //   * row maxima of half hh+1 and the rescale decision in the exp-free tail [RM0, M);
+  //   * in odd steps the workgroup barrier and the ring refill (DMA) in the tail [EW, M).
+  constexpr int M1 = KS * QB;       // MFMAs of phase 1 (K fragment ks feeds QB of them)
+  constexpr int M2 = 2 * DB * QB;   // MFMAs of phase 2 (V^T fragment (tt, db) feeds QB of them)
+  constexpr int M = M1 + M2;
+  constexpr int NP = QB * 8;        // logit pairs per step; pair k: slab k / (4 QB), unit (k / 4) % QB
+  constexpr int NE = 2 * NP;        // exp events
+  constexpr int EW = M1 + M2 / 2;   // events live in slots [0, EW): slab 0 is packed before phase 2,
+                                    // slab 1 before the second half of phase 2 (which reads it)
+  static_assert(M2 / 2 <= M1, "slab 0 would not be complete at the start of phase 2");
+  constexpr int GK = KS / 2;        // K fragments per batch (two batches per step)
+  constexpr int GV = DB;            // V^T fragments per batch (two batches per step, 2 reads each)
+  constexpr int R = 2 * GK + 4 * GV;  // LDS read instructions per step, in issue order:
+                                      //   kg[1] (GK) | vg[0] (2 GV) | vg[1] (2 GV) | kg[0] of the next step (GK)
+  constexpr int RW = EW;            // ... issued in slots [0, RW), evenly
+  constexpr int RM1 = M - 1 - QB;  // row-max slots [RM0, RM1), then QB + 1 decision slots
+  constexpr int RM0 = (EW - (M >= 32 ? 2 : 0)) < RM1 ? (EW - (M >= 32 ? 2 : 0)) : RM1 - 1;
+  static_assert(RM0 >= M1 + 1, "row maxima would read S^T before its MFMAs retire");
+  static_assert(RM1 > RM0 && RM1 + QB < M, "no room for the row maxima");
+  static_assert(LPG <= (M - EW) * 4, "ring refill does not fit the tail");
+  // read r is issued in slot r * RW / R, event j in slot j * EW / NE; reads issued before slot sl:
+  auto rd_before = [](int sl) constexpr { int n = 0; for (int r = 0; r < R; ++r) n += (r * RW / R) < sl; return n; };
 
   floatx16 sA[QB], sB[QB];
-  bf16x8 kg[2][GK], vg[2][GV];  // fragment batches in flight: LDS reads are issued a batch ahead, so
-                                // one wait covers a whole batch
+  bf16x8 kg[2][GK];          // K fragment batches
+  short4_ vh[2][GV][2];      // V^T fragment batches, as the two transpose-read halves of each fragment
+  auto v_half = [&](int tt, int db, int half, int imm) __attribute__((always_inline)) -> short4_ {
+    const unsigned char* a0 = smem + vaddr[db] + imm + 16 * tt * ROWB + half * 8 * ROWB;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0));
+  };
+
   // One pipeline step for half hh.  On entry s_cur holds S^T of half hh (masked, relative to the
-  // running max) and kg[0] the first batch of K fragments of half hh+1.  Phase 1: the matrix pipe
-  // forms S^T of half hh+1 into s_next; phase 2: it accumulates O^T += V^T P^T of half hh.
-  // TILE_START steps (even hh) first synchronise the workgroup and refill the ring; MASKED selects
-  // the rare variant for halves hh+1 that reach past the causal horizon (mask, then row max, after
-  // the matrix work); CLAMP the variant whose DMA may run past the end of the cache.
-  auto step = [&](floatx16 (&s_cur)[QB], floatx16 (&s_next)[QB], int hh, auto tile_start_tag, auto masked_tag,
+  // running max), kg[0] the first batch of K fragments of half hh+1, and kaddr/vaddr point at the
+  // tiles of halves hh+1 / hh.  ODD steps (second half of a tile) end with the workgroup barrier
+  // and the ring refill for the tiles after next; MASKED selects the rare variant for halves hh+1
+  // that reach past the causal horizon (mask, then row max, after the matrix work); CLAMP the
+  // variant whose refill may run past the end of the cache.
+  auto step = [&](floatx16 (&s_cur)[QB], floatx16 (&s_next)[QB], int hh, auto odd_tag, auto masked_tag,
                   auto clamp_tag) __attribute__((always_inline)) {
-    constexpr bool TILE_START = decltype(tile_start_tag)::value;
+    constexpr bool ODD = decltype(odd_tag)::value;
     constexpr bool MASKED = decltype(masked_tag)::value;
     const int t = hh >> 1;
-    constexpr int KIMM = TILE_START ? HALFB : 0;  // even hh: half hh+1 is the second half of tile t
-    constexpr int VIMM = TILE_START ? 0 : HALFB;  // even hh: half hh is the first half of tile t
-    int kslot_prev = 0, vslot_prev = 0;
-    if (TILE_START) {
-      // K[t+1] and V[t] were issued NV-1 tiles ago: they are the oldest group in flight
-      wait_vm<(NV - 2) * LPG>();
-      __builtin_amdgcn_s_barrier();  // ... for every wavefront; also: everyone is done reading K[t-1], V[t-1]
-      kslot_prev = kslot == 0 ? NK - 1 : kslot - 1;  // K[t-1]'s slot receives K[t+NV]
-      vslot_prev = vslot == 0 ? NV - 1 : vslot - 1;  // V[t-1]'s slot receives V[t+NV-1]
-    }
+    constexpr int KIMM = ODD ? 0 : HALFB;  // even hh: half hh+1 is the second half of tile t
+    constexpr int VIMM = ODD ? HALFB : 0;  // even hh: half hh is the first half of tile t
     float lsum[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) lsum[qb] = 0.f;
-    uintx4 pb[QB][2];  // P^T fragments: 8 bf16 per 16-key slab, as packed pairs
-    // Pair k: P = 2^(S') for two logits (exp2 x2), pack to bf16 (x1), add to the row sum of the
-    // ROUNDED values (dot2 with (1,1), x1).  The four instructions are issued as one block, with
-    // the dot2 of the PREVIOUS pair placed between the exps and the pack: that gives the
-    // transcendental results the idle cycle they need before they are read, without a no-op.
+    uintx4 pb[QB][2];      // P^T fragments: 8 bf16 per 16-key slab, as packed pairs
     unsigned pk_prev = 0;  // packed pair whose row-sum contribution is still pending (0 adds nothing)
     int qb_prev = 0;
-    auto softmax_pairs = [&](int k0, int k1) __attribute__((always_inline)) {
-#pragma unroll
-      for (int k = k0; k < k1; ++k) {
-        const int slab = k / (QB * 4), kk = k % (QB * 4);
-        const int qb = kk >> 2, j = kk & 3, r = 8 * slab + 2 * j;
-        float e0, e1;
-        unsigned pku;
-        asm volatile(
-            "v_exp_f32_e32 %0, %5\n\t"
-            "v_exp_f32_e32 %1, %6\n\t"
-            "v_dot2c_f32_bf16_e32 %3, 0x3f803f80, %4\n\t"
-            "v_cvt_pk_bf16_f32 %2, %0, %1"
-            : "=&v"(e0), "=&v"(e1), "=v"(pku), "+v"(lsum[qb_prev])
-            : "v"(pk_prev), "v"(s_cur[qb][r]), "v"(s_cur[qb][r + 1]));
-        pb[qb][slab][j] = pku;
-        pk_prev = pku;
-        qb_prev = qb;
-      }
-    };
-    auto sum_last_pair = [&]() __attribute__((always_inline)) {
-      asm volatile("v_dot2c_f32_bf16_e32 %0, 0x3f803f80, %1" : "+v"(lsum[qb_prev]) : "v"(pk_prev));
-    };
-    // ---- phase 1
-#pragma unroll
-    for (int ks = 0; ks < NS1; ++ks) {
-      if (ks == 0) {
-#pragma unroll
-        for (int j = 0; j < GK; ++j) kg[1][j] = k_frag(GK + j, KIMM);
-        wait_lds<GK>();  // kg[0] has landed
-      }
-      if (ks == GK) {
-#pragma unroll
-        for (int j = 0; j < GV; ++j) vg[0][j] = v_frag(j / DB, j % DB, VIMM);
-        wait_lds<2 * GV>();  // kg[1] has landed
-      }
-      if (TILE_START) {  // refill the slots the barrier has just freed
-        if (ks < SLABS) issue_slab(false, t + NV, kslot_prev, ks, clamp_tag);
-        else issue_slab(true, t + NV - 1, vslot_prev, ks - SLABS, clamp_tag);
-      }
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const int i = ks * QB + qb;  // MFMA index within phase 1
-        if (ks == 0)
-          mfma_qk_first(s_next[qb], kg[ks / GK][ks % GK], qf[qb][ks], negm[qb]);
-        else
-          mfma_qk(s_next[qb], kg[ks / GK][ks % GK], qf[qb][ks]);
-        __builtin_amdgcn_sched_barrier(0);
-        softmax_pairs((i * P1) / M1, ((i + 1) * P1) / M1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    // ---- phase 2
+    float ea = 0.f;        // first exp of the pair in flight
     float mx[QB], dm[QB];
     bool need_rescale = false;
-    asm volatile("s_nop 1" ::: "memory");  // vector-ALU results (P) settle before the matrix pipe reads them
-    __builtin_amdgcn_sched_barrier(0);
+    int kslot_prev = 0, vslot_prev = 0;
+
+    wait_lds<0>();  // kg[0] (fetched at the end of the previous step) has landed
 #pragma unroll
-    for (int sl = 0; sl < NS2; ++sl) {
-      const int tt = sl / DB, db = sl % DB;
-      if (sl == 0) {
-#pragma unroll
-        for (int j = 0; j < GV; ++j) vg[1][j] = v_frag((GV + j) / DB, (GV + j) % DB, VIMM);
-        wait_lds<2 * GV>();  // vg[0] has landed
+    for (int i = 0; i < M; ++i) {
+      // ---- waits and the barrier come before the MFMA of the slot
+      if (i == GK * QB) wait_lds<(rd_before(GK * QB) - GK)>();                    // kg[1]
+      if (i == M1) wait_lds<(rd_before(M1) - GK - 2 * GV)>();                     // vg[0]
+      if (i == EW) wait_lds<(rd_before(EW) - GK - 4 * GV)>();                     // vg[1]
+      if (ODD && i == EW) {
+        // Every read of K[t] and V[t] by this wave has returned.  K[t+2] and V[t+1] were issued
+        // NV-1 tiles ago: they are the oldest group in flight.
+        wait_vm<(NV - 2) * LPG>();
+        __builtin_amdgcn_s_barrier();  // ... and this holds for every wave of the workgroup
+        kslot_prev = kslot == 0 ? NK - 1 : kslot - 1;  // K[t]'s slot (kslot already names K[t+1]) takes K[t+1+NV]
+        vslot_prev = vslot;                            // V[t]'s slot takes V[t+NV]
       }
-      if (sl == GV) {
-        // first K batch of the NEXT step (half hh+2); after an even step that is a new tile, whose
-        // V tile is also the one the next even step will read
-        if (TILE_START) {
-          const int kn = kslot + 1 == NK ? 0 : kslot + 1;
-          const unsigned dk = (unsigned)((kn - kslot) * TILEB);
+      // ---- the MFMA
+      if (i < M1) {
+        const int ks = i / QB, qb = i % QB;
+        if (ks == 0)
+          mfma_qk_first(s_next[qb], kg[0][0], qf[qb][0], negm[qb]);
+        else
+          mfma_qk(s_next[qb], kg[ks / GK][ks % GK], qf[qb][ks]);
+      } else {
+        const int sl = (i - M1) / QB, qb = (i - M1) % QB, tt = sl / DB, db = sl % DB;
+        const short8_ a8 = __builtin_shufflevector(vh[sl / GV][sl % GV][0], vh[sl / GV][sl % GV][1], 0, 1, 2, 3, 4, 5, 6, 7);
+        mfma_pv(o[qb][db], __builtin_bit_cast(bf16x8, a8), __builtin_bit_cast(bf16x8, pb[qb][tt]));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- its share of everything else
+      // LDS reads
 #pragma unroll
-          for (int ks = 0; ks < KS; ++ks) kaddr[ks] += dk;
-          kslot = kn;
+      for (int r = (i * R + RW - 1) / RW; r < ((i + 1) * R + RW - 1) / RW && r < R; ++r) {  // rd_slot(r) == i
+        if (r < GK) {
+          kg[1][r] = k_frag(GK + r, KIMM);
+        } else if (r < GK + 4 * GV) {
+          const int q = r - GK, f = q / 2, half = q % 2;  // fragment f = (tt, db) of the half, in use order
+          vh[f / GV][f % GV][half] = v_half(f / DB, f % DB, half, VIMM);
         } else {
+          const int j = r - GK - 4 * GV;
+          kg[0][j] = k_frag(j, ODD ? HALFB : 0);  // kg[0] of the NEXT step (half hh+2)
+        }
+      }
+      // after an even step the next K half starts a new tile: move the K read offsets to its ring
+      // slot, a few per slot, between the last read of this tile's K and the first of the next
+      if (!ODD && i >= GK * QB && i < GK * QB + (KS + 1) / 2) {
+        const int kn = kslot + 1 == NK ? 0 : kslot + 1;
+        const unsigned dk = (unsigned)((kn - kslot) * TILEB);
+        const int a = (i - GK * QB) * 2;
+        kaddr[a] += dk;
+        if (a + 1 < KS) kaddr[a + 1] += dk;
+        if (i == GK * QB + (KS + 1) / 2 - 1) kslot = kn;
+      }
+      // exp events of half hh
+#pragma unroll
+      for (int j = (i * NE + EW - 1) / EW; j < ((i + 1) * NE + EW - 1) / EW && j < NE; ++j) {  // ev_slot(j) == i
+        const int k = j >> 1, slab = k / (QB * 4), kk = k % (QB * 4);
+        const int qb = kk >> 2, jj = kk & 3, r = 8 * slab + 2 * jj;
+        if ((j & 1) == 0) {
+          asm volatile("v_exp_f32_e32 %0, %1" : "=v"(ea) : "v"(s_cur[qb][r]));
+        } else {
+          float eb;
+          unsigned pku;
+          asm volatile(
+              "v_exp_f32_e32 %0, %4\n\t"
+              "v_dot2c_f32_bf16_e32 %2, 0x3f803f80, %3\n\t"
+              "v_cvt_pk_bf16_f32 %1, %5, %0"
+              : "=&v"(eb), "=v"(pku), "+v"(lsum[qb_prev])
+              : "v"(pk_prev), "v"(s_cur[qb][r + 1]), "v"(ea));
+          pb[qb][slab][jj] = pku;
+          pk_prev = pku;
+          qb_prev = qb;
+        }
+      }
+      if (i == EW) asm volatile("v_dot2c_f32_bf16_e32 %0, 0x3f803f80, %1" : "+v"(lsum[qb_prev]) : "v"(pk_prev));
+      // row maxima of half hh+1 (its last MFMA is at least RM0 - M1 slots old), then the decision
+      if (!MASKED && i >= RM0 && i < RM1) {
+#pragma unroll
+        for (int k = ((i - RM0) * NP) / (RM1 - RM0); k < ((i - RM0 + 1) * NP) / (RM1 - RM0); ++k) {
+          const int q2 = k >> 3, r = 2 * (k & 7);
+          if (r == 0)
+            mx[q2] = fmaxf(s_next[q2][0], s_next[q2][1]);
+          else
+            mx[q2] = fmaxf(fmaxf(mx[q2], s_next[q2][r]), s_next[q2][r + 1]);
+        }
+      }
+      if (!MASKED && i >= RM1 && i < RM1 + QB) dm[i - RM1] = pair_max(mx[i - RM1]);
+      if (!MASKED && i == RM1 + QB) need_rescale = rescale_need(dm);
+      // ring refill and the V address of the next tile (odd steps, after the barrier)
+      if (ODD && i >= EW) {
+#pragma unroll
+        for (int d = ((i - EW) * LPG) / (M - EW); d < ((i - EW + 1) * LPG) / (M - EW); ++d) {
+          if (d < SLABS) issue_slab(false, t + 1 + NV, kslot_prev, d, clamp_tag);
+          else issue_slab(true, t + NV, vslot_prev, d - SLABS, clamp_tag);
+        }
+        if (i == M - 1) {
           const int vn = vslot + 1 == NV ? 0 : vslot + 1;
           const unsigned dv = (unsigned)((vn - vslot) * TILEB);
 #pragma unroll
           for (int d2 = 0; d2 < DB; ++d2) vaddr[d2] += dv;
           vslot = vn;
         }
-#pragma unroll
-        for (int j = 0; j < GK; ++j) kg[0][j] = k_frag(j, TILE_START ? 0 : HALFB);
-        wait_lds<GK>();  // vg[1] has landed
       }
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const int i = sl * QB + qb;  // MFMA index within phase 2
-        mfma_pv(o[qb][db], vg[sl / GV][sl % GV], __builtin_bit_cast(bf16x8, pb[qb][tt]));
-        __builtin_amdgcn_sched_barrier(0);
-        if (i < H2) softmax_pairs(P1 + (i * (NP - P1)) / H2, P1 + ((i + 1) * (NP - P1)) / H2);
-        if (i == H2 - 1) sum_last_pair();  // last pending row-sum contribution
-        if (!MASKED) {
-          // row maxima of s_next (its last MFMA is at least RM0 MFMAs old), then the rescale decision
-          if (i >= RM0 && i < RM1) {
-#pragma unroll
-            for (int k = ((i - RM0) * NP) / (RM1 - RM0); k < ((i - RM0 + 1) * NP) / (RM1 - RM0); ++k) {
-              const int q2 = k >> 3, r = 2 * (k & 7);
-              if (r == 0)
-                mx[q2] = fmaxf(s_next[q2][0], s_next[q2][1]);
-              else
-                mx[q2] = fmaxf(fmaxf(mx[q2], s_next[q2][r]), s_next[q2][r + 1]);
-              asm volatile("" : "+v"(mx[q2]));
-            }
-          }
-          if (i == RM1) need_rescale = rescale_decide(mx, dm);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) l_run[qb] += lsum[qb];
@@ -513,10 +520,13 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   };
 
   if (t_begin < t_end) {
-    // prologue: K[t_begin], then the groups {K[t+1+j], V[t+j]} the steady state expects in flight
+    // Prologue.  Steady state at the top of the even step of tile t: K[t], K[t+1], V[t] are in LDS
+    // and visible, the groups {K[t+1+j], V[t+j]}, j = 1 .. NV-1, are in flight.
     issue_k(t_begin);
+    issue_k(t_begin + 1);
+    issue_v(t_begin);
 #pragma unroll
-    for (int j = 0; j < NV - 1; ++j) {
+    for (int j = 1; j < NV; ++j) {
       issue_k(t_begin + 1 + j);
       issue_v(t_begin + j);
     }
@@ -549,23 +559,24 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     int t_fast = (vis_min - 96) / BN + 1;  // first tile that is not fast (vis_min >= 1)
     if (vis_min < 96) t_fast = 0;
     if (t_fast > t_end) t_fast = t_end;
-    // ... and tiles whose refill (tile t + NV) lies entirely inside the cache need no row clamp
-    int t_nc = (Lm1 + 1) / BN - NV;
+    // ... and tiles whose refill (tile t + 1 + NV) lies entirely inside the cache need no row clamp
+    int t_nc = (Lm1 + 1) / BN - NV - 1;
     if (t_nc > t_fast) t_nc = t_fast;
     int t = t_begin;
     for (; t < t_nc; ++t) {
-      step(sA, sB, 2 * t, std::true_type{}, std::false_type{}, std::false_type{});
-      step(sB, sA, 2 * t + 1, std::false_type{}, std::false_type{}, std::false_type{});
+      step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::false_type{});
+      step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::false_type{});
     }
     for (; t < t_fast; ++t) {
-      step(sA, sB, 2 * t, std::true_type{}, std::false_type{}, std::true_type{});
-      step(sB, sA, 2 * t + 1, std::false_type{}, std::false_type{}, std::true_type{});
+      step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::true_type{});
+      step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::true_type{});
     }
     for (; t < t_end; ++t) {
-      step(sA, sB, 2 * t, std::true_type{}, std::true_type{}, std::true_type{});
-      step(sB, sA, 2 * t + 1, std::false_type{}, std::true_type{}, std::true_type{});
+      step(sA, sB, 2 * t, std::false_type{}, std::true_type{}, std::true_type{});
+      step(sB, sA, 2 * t + 1, std::true_type{}, std::true_type{}, std::true_type{});
     }
     wait_vm<0>();  // nothing of ours may still be writing LDS when the workgroup retires
+    wait_lds<0>();
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
