@@ -137,6 +137,16 @@ int kvfold_cache_view(const kvfold_cache_t* cache, int layer, void** k_dev, void
                       int64_t* row_stride_elems, int64_t* head_stride_elems);
 
 /*
+ * Rewind `layer` (-1 = every layer) to `new_len` rows, 0 = reset.  Shrink only:
+ * new_len must not exceed the current length of the layer (of any layer when
+ * layer is -1), else KVFOLD_ERR_POSITION and nothing changes.  Rows stay in HBM;
+ * the cache accumulates and never overwrites (Sec. 3.3), so re-running the
+ * steps after a rewind re-appends identical rows.  Host-only; the caller orders
+ * it against in-flight steps.
+ */
+int kvfold_cache_truncate(kvfold_cache_t* cache, int layer, int64_t new_len);
+
+/*
  * Set the host-side length of `layer` (-1 = every layer) to `new_len`.
  * new_len <= capacity; rows are left as they are in HBM.  Shrinking rewinds a
  * fold (re-running a step re-appends identical rows); growing adopts rows a

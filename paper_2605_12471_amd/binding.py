@@ -74,6 +74,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvfold_cache_view.argtypes = [vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                       ctypes.POINTER(i64), ctypes.POINTER(i64)]
     lib.kvfold_cache_view.restype = ctypes.c_int
+    lib.kvfold_cache_truncate.argtypes = [vp, ctypes.c_int, i64]
+    lib.kvfold_cache_truncate.restype = ctypes.c_int
     lib.kvfold_cache_set_length.argtypes = [vp, ctypes.c_int, i64]
     lib.kvfold_cache_set_length.restype = ctypes.c_int
     lib.kvfold_cache_set_tuning.argtypes = [vp, i32, i32]
@@ -137,6 +139,10 @@ def kvfold_cache_view(cache, layer):
     rc = load_library().kvfold_cache_view(cache, layer, ctypes.byref(k), ctypes.byref(v), ctypes.byref(rs),
                                           ctypes.byref(hs))
     return rc, k.value, v.value, rs.value, hs.value
+
+
+def kvfold_cache_truncate(cache, layer, new_len) -> int:
+    return load_library().kvfold_cache_truncate(cache, layer, new_len)
 
 
 def kvfold_cache_set_length(cache, layer, new_len) -> int:
@@ -232,6 +238,11 @@ class KvFoldCache:
         if n < 0:
             raise KvFoldError(n, "kvfold_cache_length")
         return n
+
+    def truncate(self, layer, new_len):
+        rc = kvfold_cache_truncate(self.handle, layer, new_len)
+        if rc:
+            raise KvFoldError(rc, "kvfold_cache_truncate")
 
     def set_length(self, layer, new_len):
         rc = kvfold_cache_set_length(self.handle, layer, new_len)

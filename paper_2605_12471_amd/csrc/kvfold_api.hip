@@ -365,6 +365,21 @@ int kvfold_cache_view(const kvfold_cache_t* c, int layer, void** k_dev, void** v
   return KVFOLD_OK;
 }
 
+int kvfold_cache_truncate(kvfold_cache_t* c, int layer, int64_t new_len) {
+  if (!c) return KVFOLD_ERR_INVALID_ARG;
+  if (layer < -1 || layer >= c->cfg.n_layers) return KVFOLD_ERR_BAD_LAYER;
+  if (new_len < 0) return KVFOLD_ERR_INVALID_ARG;
+  if (layer == -1) {
+    for (int64_t v : c->len)
+      if (new_len > v) return KVFOLD_ERR_POSITION;
+    for (auto& v : c->len) v = new_len;
+  } else {
+    if (new_len > c->len[(size_t)layer]) return KVFOLD_ERR_POSITION;
+    c->len[(size_t)layer] = new_len;
+  }
+  return KVFOLD_OK;
+}
+
 int kvfold_cache_set_length(kvfold_cache_t* c, int layer, int64_t new_len) {
   if (!c) return KVFOLD_ERR_INVALID_ARG;
   if (layer < -1 || layer >= c->cfg.n_layers) return KVFOLD_ERR_BAD_LAYER;

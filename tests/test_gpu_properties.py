@@ -135,11 +135,14 @@ def test_resume_from_copied_rows(H):
 
 
 def test_rewind_and_reappend(H):
-    """set_length shrinks the host-side length; re-running the step re-appends identical rows."""
+    """truncate shrinks the host-side length; re-running the step re-appends identical rows."""
     cfg = I.FoldConfig("rewind", 25, 1, 8, 2, 128, 64, 0, "bf16")
     outs, gpu = _fold(H, cfg, [64] * 4)
     try:
-        gpu.cache.set_length(0, 128)
+        assert kv.kvfold_cache_truncate(gpu.cache.handle, 0, 257) == -3   # shrink only
+        assert gpu.cache.length(0) == 256
+        gpu.cache.truncate(0, 128)
+        assert gpu.cache.length(0) == 128
         for step in (2, 3):
             q, k, v = I.chunk_qkv(cfg, 0, step, n_tokens=64, token_base=step * 64)
             assert torch.equal(gpu.step(0, q, k, v).cpu(), outs[step])
@@ -175,6 +178,9 @@ def test_errors_leave_the_cache_untouched(H):
         assert torch.equal(kview, before)
         assert kv.kvfold_cache_set_length(h, 0, 129) == -4
         assert kv.kvfold_cache_set_length(h, 3, 0) == -2
+        assert kv.kvfold_cache_truncate(h, 3, 0) == -2 and kv.kvfold_cache_truncate(h, 0, -1) == -1
+        assert kv.kvfold_cache_truncate(h, -1, 1) == -3 and kv.kvfold_cache_length(h, 0) == 128
+        assert kv.kvfold_cache_truncate(h, -1, 0) == 0 and kv.kvfold_cache_length(h, 0) == 0
         assert kv.kvfold_cache_set_tuning(h, 99, 0) == -1 and kv.kvfold_cache_set_tuning(h, kv.TUNE_UNITS_PER_WAVE, 3) == -1
         assert kv.kvfold_cache_plan(h, 0, 64)[0] == -1
     finally:
