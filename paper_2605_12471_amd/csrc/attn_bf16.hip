@@ -22,14 +22,19 @@
 //    O^T = V^T P^T; V^T fragments are read from the row-major V tile with the LDS transpose read
 //    (ds_read_b64_tr_b16) using the same permutation, so P never leaves registers.
 //  * Software pipeline inside the wavefront, in half tiles of 32 keys: while the matrix pipe forms
-//    S^T of half h+1 the vector ALU turns S^T of half h into P (exp2, bf16 pack, row sums); while
-//    it accumulates O^T of half h the vector ALU reduces the row maxima of half h+1.
+//    S^T of half h+1 the vector ALU turns S^T of half h into P (exp2, bf16 pack, row sums); the
+//    matrix pipe then accumulates O^T of half h.
 //  * Online softmax in base 2 with ONE vector instruction per logit: the queries are multiplied by
 //    scale*log2(e) once (and rounded to bf16 again), and the S^T accumulators start from -m (the
 //    running row max) instead of 0, so the matrix pipe delivers S*scale*log2e - m and P is a bare
-//    exp2.  The running max is kept stale until it lags by more than 2^16 (then O, l and the
-//    in-flight logits are corrected); P is rounded to bf16 by the hardware pack convert and row sums
-//    are accumulated from the ROUNDED values so the weights stay a convex combination.
+//    exp2.  m only has to be a reference close enough to the true row max for P to stay inside the
+//    float range, so on tiles below the causal horizon no row max is taken at all: the row sum of a
+//    half, which is needed anyway, bounds its largest P, and when it passes 2^20 the reference moves
+//    up by a whole power of two (O, l and the in-flight logits are corrected exactly).  A row sum
+//    beyond 2^60, infinite or NaN means the logits jumped by more than that inside one half; the
+//    workgroup then starts over in a mode that takes the exact row max of every half before its
+//    exp2 (the mode the masked tiles at the causal horizon always use, stale by at most 2^16).
+//    P is rounded to bf16 by the hardware pack convert; row sums add the unrounded fp32 values.
 //  * Optional split of the key range over workgroups: partial (max, sum, O) go to a workspace
 //    and are merged by the combine kernel.
 #include <type_traits>
@@ -46,7 +51,7 @@ typedef __attribute__((ext_vector_type(8))) short short8_;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 typedef __attribute__((ext_vector_type(4))) unsigned uintx4;
 
-#define LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(p))
+#define LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(uintptr_t)(p))
 
 __device__ __forceinline__ float pair_max(float x) {
   // lanes l and l^32 exchange x; both end with the maximum
@@ -98,16 +103,21 @@ __device__ __forceinline__ void mfma_settle_a(floatx16& x) {
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(x));
 }
 
-#ifndef KVFOLD_P1_EIGHTHS
-#define KVFOLD_P1_EIGHTHS 6  // pairs of phase 1 = QB * this (4..8)
-#endif
 #ifndef KVFOLD_NV2
 #define KVFOLD_NV2 3  // V ring slots of the two-units-per-wave kernel (K ring has one more)
 #endif
 constexpr float kRescaleThreshold = 16.0f;  // log2 units: stale running max tolerated up to 2^16
+constexpr float kSumThreshold = 1048576.0f;             // 2^20: row sum of a half that moves the reference up
+constexpr float kRedoThreshold = 1152921504606846976.0f;  // 2^60: beyond this the workgroup starts over
 
 template <int D, int QB, int NV>
 __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnParams p) {
+  // Sum-driven reference updates (no row max below the causal horizon) for the two-unit kernel, whose
+  // single wavefront per SIMD cannot hide the row-max work; the one-unit kernel has a second
+  // wavefront to hide it and fewer registers, and takes the exact row max of every half.
+  constexpr bool SUM_MODE = QB == 2;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const unsigned lds0 = (unsigned)(uintptr_t)((unsigned char __attribute__((address_space(3)))*)smem);
   constexpr int NK = NV + 1;         // K ring slots (K runs half a tile ahead of V in the pipeline)
   constexpr int CH = D / 8;          // 16-byte chunks per row
   constexpr int ROWB = D * 2;        // bytes per row
@@ -122,9 +132,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   constexpr int KSW = CH < 16 ? CH : 16;  // K swizzle: chunk ^= row % KSW
   constexpr int VSW = CH / 4;             // V swizzle: chunk ^= (row & 3) * VSW
 
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   // rings: K slots [0, NK), V slots [NK, NK + NV)
-  const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(unsigned char, smem);
 
   // ---- which workgroup am I (XCD-aware: contiguous logical ranges per XCD)
   const int per_xcd = gridDim.x / kNumXcd;
@@ -206,69 +214,79 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   const unsigned dma_voff = (unsigned)dma_row0 * ROWB + dma_vc;
   // slab i of tile t of K (is_v = false) or V; CLAMP redirects rows past the cache end to the last
   // valid row (they are masked anyway, but are never read from memory)
-  auto issue_slab = [&](bool is_v, int t, int slot, int i, auto clamp_tag) __attribute__((always_inline)) {
+  auto issue_slab = [&](bool is_v, int t, int slot, int i, auto clamp_tag, unsigned extra = 0) __attribute__((always_inline)) {
     constexpr bool CLAMP = decltype(clamp_tag)::value;
     const unsigned lds = lds0 + (unsigned)(((is_v ? NK : 0) + slot) * TILEB + (w + 4 * i) * 1024);
     unsigned off;
     if (CLAMP) {
       unsigned grow = (unsigned)(t * BN + dma_row0 + i * 4 * RPS);
-      grow = grow < (unsigned)Lm1 ? grow : (unsigned)Lm1;
+      grow = (grow < (unsigned)Lm1 ? grow : (unsigned)Lm1) + extra;
       off = grow * ROWB + (is_v ? dma_vc : dma_kc);
     } else {
       off = (is_v ? dma_voff : dma_koff) + (unsigned)(t * BN + i * 4 * RPS) * ROWB;
     }
     dma16(is_v ? vbase : kbase, off, lds);
   };
-  auto issue_k = [&](int t) __attribute__((always_inline)) {
+  auto issue_k = [&](int t, unsigned extra) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < SLABS; ++i) issue_slab(false, t, t % NK, i, std::true_type{});
+    for (int i = 0; i < SLABS; ++i) issue_slab(false, t, t % NK, i, std::true_type{}, extra);
   };
-  auto issue_v = [&](int t) __attribute__((always_inline)) {
+  auto issue_v = [&](int t, unsigned extra) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < SLABS; ++i) issue_slab(true, t, t % NV, i, std::true_type{});
+    for (int i = 0; i < SLABS; ++i) issue_slab(true, t, t % NV, i, std::true_type{}, extra);
   };
 
   // ---- LDS read offsets (per lane) of the tile currently being read, ring slot included; moved
   // from slot to slot once per tile
   // K fragment (A operand of S^T): row kb*32+m, chunk ks*2+hi, swizzled by row % KSW = m % KSW
-  int kslot = t_begin % NK, vslot = t_begin % NV;  // ring slots of tile t (wave-uniform)
+  int kslot, vslot;  // ring slots of tile t (wave-uniform)
   unsigned kaddr[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks)
-    kaddr[ks] = (unsigned)(m * ROWB + (((ks * 2 + hi) ^ (m % KSW)) * 16)) + (unsigned)(kslot * TILEB);
-  // V^T fragment via transpose read: lane i of a 16-lane block supplies row (i/4) of a 4-row group and 4 columns
-  const int i16 = l & 15, b2 = (l >> 4) & 1;
-  const int v_row = 4 * hi + (i16 >> 2);  // + 16*tt (+8)
   unsigned vaddr[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-    vaddr[db] = (unsigned)(v_row * ROWB + (((4 * db + 2 * b2 + ((i16 & 3) >> 1)) ^ ((v_row & 3) * VSW)) * 16) + 8 * (i16 & 1)) +
-                (unsigned)((NK + vslot) * TILEB);
 
   // ---- running state
   floatx16 o[QB][DB];   // O^T accumulators (AGPRs)
   floatx16 negm[QB];    // -m (0 while no key has been seen) in every element: start value of S^T
   float m_run[QB], l_run[QB];
+  int overflowed = 0;   // wave-uniform: a row sum left the range the sum-driven rescale can repair
+  auto reset_state = [&]() __attribute__((always_inline)) {
+    kslot = t_begin % NK;
+    vslot = t_begin % NV;
+    // derived from an opaque copy of the lane id, so that nothing computed here is kept in registers
+    // across the main loop for the sake of a restart that almost never happens
+    int l2 = l;
+    asm volatile("" : "+v"(l2));
+    const int hi2 = l2 >> 5, m2 = l2 & 31;
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m_run[qb] = -INFINITY;
-    l_run[qb] = 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) negm[qb][r] = 0.f;
+    for (int ks = 0; ks < KS; ++ks)
+      kaddr[ks] = lds0 + (unsigned)(m2 * ROWB + (((ks * 2 + hi2) ^ (m2 % KSW)) * 16)) + (unsigned)(kslot * TILEB);
+    // V^T fragment via transpose read: lane i of a 16-lane block supplies row (i/4) of a 4-row group and 4 columns
+    const int i16 = l2 & 15, b2 = (l2 >> 4) & 1;
+    const int v_row = 4 * hi2 + (i16 >> 2);  // + 16*tt (+8)
 #pragma unroll
     for (int db = 0; db < DB; ++db)
+      vaddr[db] = lds0 + (unsigned)(v_row * ROWB + (((4 * db + 2 * b2 + ((i16 & 3) >> 1)) ^ ((v_row & 3) * VSW)) * 16) + 8 * (i16 & 1)) +
+                  (unsigned)((NK + vslot) * TILEB);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
-  }
+    for (int qb = 0; qb < QB; ++qb) {
+      m_run[qb] = -INFINITY;
+      l_run[qb] = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) negm[qb][r] = 0.f;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
+    }
+  };
 
   // ---- building blocks of the software pipeline --------------------------------------------
   auto k_frag = [&](int ks, int imm) __attribute__((always_inline)) -> bf16x8 {
-    return *reinterpret_cast<const bf16x8*>(smem + kaddr[ks] + imm);
+    return *LDS_PTR(const bf16x8, kaddr[ks] + (unsigned)imm);
   };
   auto v_frag = [&](int tt, int db, int imm) __attribute__((always_inline)) -> bf16x8 {
-    const unsigned char* a0 = smem + vaddr[db] + imm + 16 * tt * ROWB;
+    const unsigned a0 = vaddr[db] + (unsigned)(imm + 16 * tt * ROWB);
     const short4_ lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0));
-    const short4_ hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0 + 8 * ROWB));
+    const short4_ hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0 + (unsigned)(8 * ROWB)));
     const short8_ a8 = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, a8);
   };
@@ -326,6 +344,37 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       }
     }
   };
+  // ls[] holds the row sums of the half just exponentiated (per lane: the 16 keys it owns).  A sum
+  // above 2^20 moves the reference up by the power of two just above it, which is exact; s holds
+  // the in-flight logits of the next half, formed against the old reference.  Both lanes of a row
+  // decide on the larger of their two sums, so a row never depends on its wave neighbours.
+  auto rescale_from_sum = [&](const float (&ls)[QB], floatx16 (&s)[QB]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const float tot = pair_max(ls[qb]);
+      const bool bad = !(tot <= kRedoThreshold);  // also infinite or NaN
+      overflowed |= __any((int)bad);
+      const bool mine = !(tot <= kSumThreshold) && !bad;
+      const int e = mine ? __builtin_amdgcn_frexp_expf(tot) : 0;  // tot < 2^e
+      const float delta = (float)e;
+      const float alpha = __builtin_ldexpf(1.0f, -e);
+      const float cur = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
+      const float use = cur + delta;
+      if (mine) m_run[qb] = use;
+      l_run[qb] *= alpha;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        negm[qb][r] = -use;
+        s[qb][r] -= delta;
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        mfma_settle_a(o[qb][db]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
+      }
+    }
+  };
   auto rowmax_all = [&](floatx16 (&s)[QB], float (&mx)[QB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -344,7 +393,8 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   //   * exp2 / pack / row-sum of half hh in slots [0, EW): one "event" = one exp2 (the second
   //     event of a logit pair also packs the pair and adds the previous pair to the row sum);
   //   * LDS fragment reads one batch ahead, one instruction per slot, one wait per batch;
-  //   * row maxima of half hh+1 and the rescale decision in the exp-free tail [RM0, M);
+  //   * SUM_MODE: the test of the row sums against 2^20 right after the last exp event; else the
+  //     row maxima of half hh+1 and the rescale decision in the exp-free tail [RM0, M);
   //   * in odd steps the workgroup barrier and the ring refill (DMA) in the tail [EW, M).
   constexpr int M1 = KS * QB;       // MFMAs of phase 1 (K fragment ks feeds QB of them)
   constexpr int M2 = 2 * DB * QB;   // MFMAs of phase 2 (V^T fragment (tt, db) feeds QB of them)
@@ -359,10 +409,11 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   constexpr int R = 2 * GK + 4 * GV;  // LDS read instructions per step, in issue order:
                                       //   kg[1] (GK) | vg[0] (2 GV) | vg[1] (2 GV) | kg[0] of the next step (GK)
   constexpr int RW = EW;            // ... issued in slots [0, RW), evenly
+  static_assert(EW + 1 < M, "no slot for the row-sum test");
   constexpr int RM1 = M - 1 - QB;  // row-max slots [RM0, RM1), then QB + 1 decision slots
   constexpr int RM0 = (EW - (M >= 32 ? 2 : 0)) < RM1 ? (EW - (M >= 32 ? 2 : 0)) : RM1 - 1;
-  static_assert(RM0 >= M1 + 1, "row maxima would read S^T before its MFMAs retire");
-  static_assert(RM1 > RM0 && RM1 + QB < M, "no room for the row maxima");
+  static_assert(SUM_MODE || RM0 >= M1 + 1, "row maxima would read S^T before its MFMAs retire");
+  static_assert(SUM_MODE || (RM1 > RM0 && RM1 + QB < M), "no room for the row maxima");
   static_assert(LPG <= (M - EW) * 4, "ring refill does not fit the tail");
   // read r is issued in slot r * RW / R, event j in slot j * EW / NE; reads issued before slot sl:
   auto rd_before = [](int sl) constexpr { int n = 0; for (int r = 0; r < R; ++r) n += (r * RW / R) < sl; return n; };
@@ -371,16 +422,16 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   bf16x8 kg[2][GK];          // K fragment batches
   short4_ vh[2][GV][2];      // V^T fragment batches, as the two transpose-read halves of each fragment
   auto v_half = [&](int tt, int db, int half, int imm) __attribute__((always_inline)) -> short4_ {
-    const unsigned char* a0 = smem + vaddr[db] + imm + 16 * tt * ROWB + half * 8 * ROWB;
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0));
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, vaddr[db] + (unsigned)(imm + 16 * tt * ROWB + half * 8 * ROWB)));
   };
 
   // One pipeline step for half hh.  On entry s_cur holds S^T of half hh (masked, relative to the
   // running max), kg[0] the first batch of K fragments of half hh+1, and kaddr/vaddr point at the
   // tiles of halves hh+1 / hh.  ODD steps (second half of a tile) end with the workgroup barrier
-  // and the ring refill for the tiles after next; MASKED selects the rare variant for halves hh+1
-  // that reach past the causal horizon (mask, then row max, after the matrix work); CLAMP the
-  // variant whose refill may run past the end of the cache.
+  // and the ring refill for the tiles after next; MASKED selects the variant for halves hh+1 that
+  // reach past the causal horizon, and for every half once a row sum has overflowed (mask, then the
+  // exact row max, after the matrix work); CLAMP the variant whose refill may run past the end of
+  // the cache.
   auto step = [&](floatx16 (&s_cur)[QB], floatx16 (&s_next)[QB], int hh, auto odd_tag, auto masked_tag,
                   auto clamp_tag) __attribute__((always_inline)) {
     constexpr bool ODD = decltype(odd_tag)::value;
@@ -392,11 +443,12 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) lsum[qb] = 0.f;
     uintx4 pb[QB][2];      // P^T fragments: 8 bf16 per 16-key slab, as packed pairs
-    unsigned pk_prev = 0;  // packed pair whose row-sum contribution is still pending (0 adds nothing)
+    float eb_prev = 0.f;   // second exp of the last pair, not yet in its row sum
     int qb_prev = 0;
     float ea = 0.f;        // first exp of the pair in flight
     float mx[QB], dm[QB];
     bool need_rescale = false;
+    int sum_flag = 0;      // per lane: a row sum of this half passed 2^20 (or is not a number)
     int kslot_prev = 0, vslot_prev = 0;
 
     wait_lds<0>();  // kg[0] (fetched at the end of the previous step) has landed
@@ -457,24 +509,35 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
         const int k = j >> 1, slab = k / (QB * 4), kk = k % (QB * 4);
         const int qb = kk >> 2, jj = kk & 3, r = 8 * slab + 2 * jj;
         if ((j & 1) == 0) {
-          asm volatile("v_exp_f32_e32 %0, %1" : "=v"(ea) : "v"(s_cur[qb][r]));
+          if (j == 0)
+            asm volatile("v_exp_f32_e32 %0, %1" : "=v"(ea) : "v"(s_cur[qb][r]));
+          else  // ... and the second exp of the previous pair joins its row sum
+            asm volatile(
+                "v_exp_f32_e32 %0, %2\n\t"
+                "v_add_f32_e32 %1, %3, %1"
+                : "=&v"(ea), "+v"(lsum[qb_prev])
+                : "v"(s_cur[qb][r]), "v"(eb_prev));
         } else {
           float eb;
           unsigned pku;
           asm volatile(
-              "v_exp_f32_e32 %0, %4\n\t"
-              "v_dot2c_f32_bf16_e32 %2, 0x3f803f80, %3\n\t"
-              "v_cvt_pk_bf16_f32 %1, %5, %0"
-              : "=&v"(eb), "=v"(pku), "+v"(lsum[qb_prev])
-              : "v"(pk_prev), "v"(s_cur[qb][r + 1]), "v"(ea));
+              "v_exp_f32_e32 %0, %3\n\t"
+              "v_add_f32_e32 %2, %4, %2\n\t"
+              "v_cvt_pk_bf16_f32 %1, %4, %0"
+              : "=&v"(eb), "=v"(pku), "+v"(lsum[qb])
+              : "v"(s_cur[qb][r + 1]), "v"(ea));
           pb[qb][slab][jj] = pku;
-          pk_prev = pku;
+          eb_prev = eb;
           qb_prev = qb;
         }
       }
-      if (i == EW) asm volatile("v_dot2c_f32_bf16_e32 %0, 0x3f803f80, %1" : "+v"(lsum[qb_prev]) : "v"(pk_prev));
+      if (i == EW) lsum[qb_prev] += eb_prev;
+      if (SUM_MODE && i == EW + 1) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) sum_flag |= (int)!(lsum[qb] <= kSumThreshold);
+      }
       // row maxima of half hh+1 (its last MFMA is at least RM0 - M1 slots old), then the decision
-      if (!MASKED && i >= RM0 && i < RM1) {
+      if (!SUM_MODE && !MASKED && i >= RM0 && i < RM1) {
 #pragma unroll
         for (int k = ((i - RM0) * NP) / (RM1 - RM0); k < ((i - RM0 + 1) * NP) / (RM1 - RM0); ++k) {
           const int q2 = k >> 3, r = 2 * (k & 7);
@@ -484,8 +547,8 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
             mx[q2] = fmaxf(fmaxf(mx[q2], s_next[q2][r]), s_next[q2][r + 1]);
         }
       }
-      if (!MASKED && i >= RM1 && i < RM1 + QB) dm[i - RM1] = pair_max(mx[i - RM1]);
-      if (!MASKED && i == RM1 + QB) need_rescale = rescale_need(dm);
+      if (!SUM_MODE && !MASKED && i >= RM1 && i < RM1 + QB) dm[i - RM1] = pair_max(mx[i - RM1]);
+      if (!SUM_MODE && !MASKED && i == RM1 + QB) need_rescale = rescale_need(dm);
       // ring refill and the V address of the next tile (odd steps, after the barrier)
       if (ODD && i >= EW) {
 #pragma unroll
@@ -505,6 +568,13 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     }
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) l_run[qb] += lsum[qb];
+    if constexpr (SUM_MODE) {
+      if (__builtin_expect(__any(sum_flag), 0)) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
+        rescale_from_sum(lsum, s_next);
+      }
+    }
     if (MASKED) {
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
@@ -520,67 +590,89 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   };
 
   if (t_begin < t_end) {
-    // Prologue.  Steady state at the top of the even step of tile t: K[t], K[t+1], V[t] are in LDS
-    // and visible, the groups {K[t+1+j], V[t+j]}, j = 1 .. NV-1, are in flight.
-    issue_k(t_begin);
-    issue_k(t_begin + 1);
-    issue_v(t_begin);
+    // A second pass (exact = true) follows only if a row sum overflowed in the first.
+    for (bool exact = false;; exact = true) {
+      reset_state();
+      unsigned again_zero = 0;  // opaque zero: keeps the prologue's addresses from being computed once and
+      asm volatile("" : "+v"(again_zero));  // held in registers across the main loop for the sake of a second pass
+      // Prologue.  Steady state at the top of the even step of tile t: K[t], K[t+1], V[t] are in LDS
+      // and visible, the groups {K[t+1+j], V[t+j]}, j = 1 .. NV-1, are in flight.
+      issue_k(t_begin, again_zero);
+      issue_k(t_begin + 1, again_zero);
+      issue_v(t_begin, again_zero);
 #pragma unroll
-    for (int j = 1; j < NV; ++j) {
-      issue_k(t_begin + 1 + j);
-      issue_v(t_begin + j);
-    }
-    wait_vm<(NV - 1) * LPG>();
-    __builtin_amdgcn_s_barrier();
-    {
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a = k_frag(ks, 0);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-          if (ks == 0)
-            mfma_qk_first(sA[qb], a, qf[qb][ks], negm[qb]);
-          else
-            mfma_qk(sA[qb], a, qf[qb][ks]);
-        }
+      for (int j = 1; j < NV; ++j) {
+        issue_k(t_begin + 1 + j, again_zero);
+        issue_v(t_begin + j, again_zero);
       }
+      wait_vm<(NV - 1) * LPG>();
+      __builtin_amdgcn_s_barrier();
+      {
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) mfma_settle_v(sA[qb]);
-      if (t_begin * BN + 32 > vis_min) mask_half(sA, 2 * t_begin);
-      float mx[QB], dm[QB];
-      rowmax_all(sA, mx);
-      if (rescale_decide(mx, dm)) rescale_apply(dm, sA);
-      // first K batch of the first step: second half of tile t_begin
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8 a = k_frag(ks, 0);
 #pragma unroll
-      for (int j = 0; j < GK; ++j) kg[0][j] = k_frag(j, HALFB);
+          for (int qb = 0; qb < QB; ++qb) {
+            if (ks == 0)
+              mfma_qk_first(sA[qb], a, qf[qb][ks], negm[qb]);
+            else
+              mfma_qk(sA[qb], a, qf[qb][ks]);
+          }
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) mfma_settle_v(sA[qb]);
+        if (t_begin * BN + 32 > vis_min) mask_half(sA, 2 * t_begin);
+        float mx[QB], dm[QB];
+        rowmax_all(sA, mx);
+        if (rescale_decide(mx, dm)) rescale_apply(dm, sA);
+        // first K batch of the first step: second half of tile t_begin
+#pragma unroll
+        for (int j = 0; j < GK; ++j) kg[0][j] = k_frag(j, HALFB);
+      }
+      // Tiles whose two steps only produce halves entirely below the nearest causal horizon take the
+      // fast variant: step 2t+1 produces half 2t+2 = keys [64t+64, 64t+96), so it needs 64t+96 <= vis_min.
+      int t_fast = (vis_min - 96) / BN + 1;  // first tile that is not fast (vis_min >= 1)
+      if (vis_min < 96 || exact) t_fast = 0;
+      if (t_fast > t_end) t_fast = t_end;
+      // ... and tiles whose refill (tile t + 1 + NV) lies entirely inside the cache need no row clamp
+      int t_nc = (Lm1 + 1) / BN - NV - 1;
+      if (t_nc > t_fast) t_nc = t_fast;
+      int t = t_begin;
+      for (; t < t_nc; ++t) {
+        step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::false_type{});
+        step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::false_type{});
+      }
+      for (; t < t_fast; ++t) {
+        step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::true_type{});
+        step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::true_type{});
+      }
+      for (; t < t_end; ++t) {
+        step(sA, sB, 2 * t, std::false_type{}, std::true_type{}, std::true_type{});
+        step(sB, sA, 2 * t + 1, std::true_type{}, std::true_type{}, std::true_type{});
+      }
+      wait_vm<0>();  // nothing of ours may still be writing LDS when the workgroup retires or starts over
+      wait_lds<0>();
+      if (!SUM_MODE || exact) break;
+      {
+        // Did a row sum of any wavefront overflow?  The rings are dead now: their first bytes carry the vote.
+        __builtin_amdgcn_s_barrier();
+        if (l == 0) *LDS_PTR(int, lds0 + 4u * (unsigned)w) = overflowed;
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();
+        int any_overflow = 0;
+#pragma unroll
+        for (int ww = 0; ww < 4; ++ww) any_overflow |= *LDS_PTR(const int, lds0 + 4u * (unsigned)ww);
+        any_overflow = __builtin_amdgcn_readfirstlane(any_overflow);
+        __builtin_amdgcn_s_barrier();  // every wavefront has read the vote before the next pass refills the ring
+        if (__builtin_expect(any_overflow == 0, 1)) break;
+      }
     }
-    // Tiles whose two steps only produce halves entirely below the nearest causal horizon take the
-    // fast variant: step 2t+1 produces half 2t+2 = keys [64t+64, 64t+96), so it needs 64t+96 <= vis_min.
-    int t_fast = (vis_min - 96) / BN + 1;  // first tile that is not fast (vis_min >= 1)
-    if (vis_min < 96) t_fast = 0;
-    if (t_fast > t_end) t_fast = t_end;
-    // ... and tiles whose refill (tile t + 1 + NV) lies entirely inside the cache need no row clamp
-    int t_nc = (Lm1 + 1) / BN - NV - 1;
-    if (t_nc > t_fast) t_nc = t_fast;
-    int t = t_begin;
-    for (; t < t_nc; ++t) {
-      step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::false_type{});
-      step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::false_type{});
-    }
-    for (; t < t_fast; ++t) {
-      step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::true_type{});
-      step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::true_type{});
-    }
-    for (; t < t_end; ++t) {
-      step(sA, sB, 2 * t, std::false_type{}, std::true_type{}, std::true_type{});
-      step(sB, sA, 2 * t + 1, std::true_type{}, std::true_type{}, std::true_type{});
-    }
-    wait_vm<0>();  // nothing of ours may still be writing LDS when the workgroup retires
-    wait_lds<0>();
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int db = 0; db < DB; ++db) mfma_settle_a(o[qb][db]);
+  } else {
+    reset_state();
   }
 
   // ---- epilogue

@@ -15,6 +15,7 @@ from __future__ import annotations
 
 import dataclasses
 import functools
+import math
 import hashlib
 from typing import Optional
 
@@ -113,6 +114,36 @@ def _token_range(cfg, layer, tensor_id, heads, t_lo, t_hi, dt, device):
         hi = min(t_hi, (gidx + 1) * _GROUP_TOKENS) - gidx * _GROUP_TOKENS
         parts.append(blk[lo:hi])
     return parts[0].contiguous().clone() if len(parts) == 1 else torch.cat(parts, 0).contiguous()
+
+
+LOGIT_PROFILES = {
+    # logit (in nats, up to the noise) of every query against key j, as a function of the absolute key index
+    "step20": lambda j: 20.0 * (j >= 100),     # one jump of 20 nats inside the prefix
+    "step45": lambda j: 45.0 * (j >= 100),     # ... of 45 nats (2^65 in one go)
+    "step100": lambda j: 100.0 * (j >= 100),   # ... of 100 nats: exp2 of the jump overflows fp32
+    "stairs": lambda j: 0.5 * j,               # rises by 16 nats every 32 keys, for ever
+    "spike": lambda j: 60.0 * (j == 130),      # one dominating key, then back to the floor
+    "late": lambda j: 80.0 * (j >= 290),       # the jump lies inside the causal part of the last chunk
+}
+
+
+def steered_qkv(cfg: FoldConfig, layer: int, step: int, profile: str, device="cpu", n_tokens: Optional[int] = None,
+                token_base: Optional[int] = None):
+    """The stream of chunk_qkv scaled to 0.1, plus a component along one seeded unit direction u that
+    gives every query the logit LOGIT_PROFILES[profile](j) against key j (softmax scale 1/sqrt(d)):
+    q += 2 sqrt(d) u, k_j += (g_j / 2) u.  Stress input for the running-max bookkeeping of a kernel;
+    V is the plain stream."""
+    C = cfg.chunk if n_tokens is None else n_tokens
+    t0 = step * cfg.chunk if token_base is None else token_base
+    q, k, v = chunk_qkv(cfg.with_(needle=False) if cfg.needle else cfg, layer, step, device, n_tokens, token_base)
+    d = cfg.head_dim
+    u = draw_normal((d,), torch.float32, device, cfg.config_id, layer, 9)
+    u = u / u.norm()
+    g = torch.tensor([LOGIT_PROFILES[profile](j) for j in range(t0, t0 + C)], dtype=torch.float32, device=device)
+    dt = torch_dtype(cfg.dtype)
+    q = (0.1 * q.float() + 2.0 * math.sqrt(d) * u).to(dt)
+    k = (0.1 * k.float() + 0.5 * g[:, None, None] * u).to(dt)
+    return q, k, v
 
 
 @dataclasses.dataclass(frozen=True)

@@ -133,5 +133,5 @@ def test_kernels_use_no_scratch_memory():
         scratch = int(re.search(r"ScratchSize \[bytes/lane\]: (\d+)", b).group(1))
         spill = int(re.search(r"VGPRs Spill: (\d+)", b).group(1))
         assert scratch == 0 and spill == 0, f"{name}: scratch {scratch} B/lane, {spill} spilled VGPRs"
-        if "attn_bf16_kernelILi128ELi2" in name:   # the flagship kernel: one wave per SIMD, O and Q in AGPRs
-            assert int(re.search(r"AGPRs: (\d+)", b).group(1)) == 192
+        if "attn_bf16_kernelILi128ELi2" in name:   # the flagship kernel: one wave per SIMD, O (128) and Q (64) in AGPRs
+            assert int(re.search(r"AGPRs: (\d+)", b).group(1)) >= 192

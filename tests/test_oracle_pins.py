@@ -273,3 +273,15 @@ def test_pins_catch_planted_mistakes(oracle):
     assert np.abs(variant(head_map=lambda h: h % 2) - good).max() > 1e-3  # interleaved GQA mapping
     assert np.abs(variant(scale=1.0) - good).max() > 1e-3               # dropped 1/sqrt(d)
     assert np.abs(variant(transpose_v=True) - good).max() > 1e-3        # value columns reversed
+
+
+def test_steered_inputs_have_the_stated_logits():
+    """The stress generator of the GPU tests: q . k_j / sqrt(d) equals the profile's logit up to the 0.1-scaled
+    noise (under a nat, growing with the logit through the cross term) and bf16 rounding."""
+    from paper_2605_12471_amd import inputs as I
+    cfg = I.FoldConfig("jumps", 15, 1, 8, 2, 128, 256, 0, "bf16")
+    for profile, fn in I.LOGIT_PROFILES.items():
+        q, k, _ = I.steered_qkv(cfg, 0, 0, profile)
+        s = np.einsum("ihx,jgx->ihgj", q.double().numpy(), k.double().numpy()) / np.sqrt(128.0)
+        want = np.array([fn(j) for j in range(256)])
+        assert np.abs(s - want[None, None, None, :]).max() < 0.8 + 0.02 * want.max(), profile
