@@ -97,7 +97,7 @@ Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
       // Short prefix: the causal part makes late token blocks up to twice as long as early ones.  If
       // the one-unit-per-wave grid is resident at once (two workgroups per CU) pair heavy with light.
       const int64_t wgs1 = (int64_t)f.n_kv_heads * ((pl.units_per_head + kUnitsPerWg - 1) / kUnitsPerWg);
-      if (len_after < 7 * (int64_t)n_tokens && wgs1 <= 2 * (int64_t)c->n_cu && wgs1 > (int64_t)c->n_cu) {
+      if (len_after < 4 * (int64_t)n_tokens && wgs1 <= 2 * (int64_t)c->n_cu && wgs1 > (int64_t)c->n_cu) {
         upw = 1;
         pl.pair_order = 1;
       }
