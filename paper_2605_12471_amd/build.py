@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    # the attention kernels unroll a 32-slot software pipeline by pragma; before the per-slot conditions
+    # fold, its body is larger than the default size limit for pragma-forced unrolling
+    "-mllvm", "-pragma-unroll-threshold=100000",
     # the compiler's per-kernel register / scratch report is kept next to the library
     "-Rpass-analysis=kernel-resource-usage",
 ]

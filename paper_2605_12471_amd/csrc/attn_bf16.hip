@@ -403,7 +403,13 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   constexpr int NE = 2 * NP;        // exp events
   constexpr int EW = M1 + M2 / 2;   // events live in slots [0, EW): slab 0 is packed before phase 2,
                                     // slab 1 before the second half of phase 2 (which reads it)
-  static_assert(M2 / 2 <= M1, "slab 0 would not be complete at the start of phase 2");
+  // SUM_MODE: the first NEAR events of a half (all in slab 0) are done EARLY, in the tail slots
+  // [EW, M) of the step before, as soon as its S^T is complete; with them every slot of a step has
+  // the same share of exp2 work.
+  constexpr int NEAR = SUM_MODE ? (NE * (M - EW) / M) & ~1 : 0;
+  constexpr int NMAIN = NE - NEAR;  // events of the half done in its own step, in slots [0, EW)
+  static_assert(NEAR <= NE / 2, "early events must stay inside slab 0");
+  static_assert(NEAR + (M1 * NMAIN + EW - 1) / EW >= NE / 2, "slab 0 would not be complete at the start of phase 2");
   constexpr int GK = KS / 2;        // K fragments per batch (two batches per step)
   constexpr int GV = DB;            // V^T fragments per batch (two batches per step, 2 reads each)
   constexpr int R = 2 * GK + 4 * GV;  // LDS read instructions per step, in issue order:
@@ -419,6 +425,51 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   auto rd_before = [](int sl) constexpr { int n = 0; for (int r = 0; r < R; ++r) n += (r * RW / R) < sl; return n; };
 
   floatx16 sA[QB], sB[QB];
+  uintx4 pb[QB][2];      // P^T fragments: 8 bf16 per 16-key slab, as packed pairs
+  float lsum_early[QB];  // row sums of the early events of the half that the next step finishes
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) lsum_early[qb] = 0.f;
+  // One exp event of a half whose logits are in s: event j covers logit j of the half's 2 NP, in
+  // pairs; the second event of a pair also packs the pair into its P^T slot and the first adds the
+  // previous pair's second exp to the row sum (`first`: there is none pending).
+  float ev_a = 0.f, ev_b = 0.f;  // first exp of the pair in flight; second exp not yet in its row sum
+  int ev_qb = 0;
+  auto exp_event = [&](const floatx16 (&s)[QB], float (&ls)[QB], int j, bool first) __attribute__((always_inline)) {
+    const int k = j >> 1, slab = k / (QB * 4), kk = k % (QB * 4);
+    const int qb = kk >> 2, jj = kk & 3, r = 8 * slab + 2 * jj;
+    if ((j & 1) == 0) {
+      if (first)
+        asm volatile("v_exp_f32_e32 %0, %1" : "=v"(ev_a) : "v"(s[qb][r]));
+      else
+        asm volatile(
+            "v_exp_f32_e32 %0, %2\n\t"
+            "v_add_f32_e32 %1, %3, %1"
+            : "=&v"(ev_a), "+v"(ls[ev_qb])
+            : "v"(s[qb][r]), "v"(ev_b));
+    } else {
+      float eb;
+      unsigned pku;
+      asm volatile(
+          "v_exp_f32_e32 %0, %3\n\t"
+          "v_add_f32_e32 %2, %4, %2\n\t"
+          "v_cvt_pk_bf16_f32 %1, %4, %0"
+          : "=&v"(eb), "=v"(pku), "+v"(ls[qb])
+          : "v"(s[qb][r + 1]), "v"(ev_a));
+      pb[qb][slab][jj] = pku;
+      ev_b = eb;
+      ev_qb = qb;
+    }
+  };
+  // the early events of a half all at once (prologue, masked steps, and again after a sum-driven shift)
+  auto early_events = [&](const floatx16 (&s)[QB]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) lsum_early[qb] = 0.f;
+    if (NEAR > 0) {
+#pragma unroll
+      for (int j = 0; j < NEAR; ++j) exp_event(s, lsum_early, j, j == 0);
+      lsum_early[ev_qb] += ev_b;
+    }
+  };
   bf16x8 kg[2][GK];          // K fragment batches
   short4_ vh[2][GV][2];      // V^T fragment batches, as the two transpose-read halves of each fragment
   auto v_half = [&](int tt, int db, int half, int imm) __attribute__((always_inline)) -> short4_ {
@@ -439,13 +490,12 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     const int t = hh >> 1;
     constexpr int KIMM = ODD ? 0 : HALFB;  // even hh: half hh+1 is the second half of tile t
     constexpr int VIMM = ODD ? HALFB : 0;  // even hh: half hh is the first half of tile t
-    float lsum[QB];
+    float lsum[QB], lsum_next[QB];  // row sums of half hh (early part included) and of the early part of hh+1
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) lsum[qb] = 0.f;
-    uintx4 pb[QB][2];      // P^T fragments: 8 bf16 per 16-key slab, as packed pairs
-    float eb_prev = 0.f;   // second exp of the last pair, not yet in its row sum
-    int qb_prev = 0;
-    float ea = 0.f;        // first exp of the pair in flight
+    for (int qb = 0; qb < QB; ++qb) {
+      lsum[qb] = lsum_early[qb];
+      lsum_next[qb] = 0.f;
+    }
     float mx[QB], dm[QB];
     bool need_rescale = false;
     int sum_flag = 0;      // per lane: a row sum of this half passed 2^20 (or is not a number)
@@ -503,35 +553,18 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
         if (a + 1 < KS) kaddr[a + 1] += dk;
         if (i == GK * QB + (KS + 1) / 2 - 1) kslot = kn;
       }
-      // exp events of half hh
+      // exp events of half hh ...
+      if (i == EW) lsum[ev_qb] += ev_b;
 #pragma unroll
-      for (int j = (i * NE + EW - 1) / EW; j < ((i + 1) * NE + EW - 1) / EW && j < NE; ++j) {  // ev_slot(j) == i
-        const int k = j >> 1, slab = k / (QB * 4), kk = k % (QB * 4);
-        const int qb = kk >> 2, jj = kk & 3, r = 8 * slab + 2 * jj;
-        if ((j & 1) == 0) {
-          if (j == 0)
-            asm volatile("v_exp_f32_e32 %0, %1" : "=v"(ea) : "v"(s_cur[qb][r]));
-          else  // ... and the second exp of the previous pair joins its row sum
-            asm volatile(
-                "v_exp_f32_e32 %0, %2\n\t"
-                "v_add_f32_e32 %1, %3, %1"
-                : "=&v"(ea), "+v"(lsum[qb_prev])
-                : "v"(s_cur[qb][r]), "v"(eb_prev));
-        } else {
-          float eb;
-          unsigned pku;
-          asm volatile(
-              "v_exp_f32_e32 %0, %3\n\t"
-              "v_add_f32_e32 %2, %4, %2\n\t"
-              "v_cvt_pk_bf16_f32 %1, %4, %0"
-              : "=&v"(eb), "=v"(pku), "+v"(lsum[qb])
-              : "v"(s_cur[qb][r + 1]), "v"(ea));
-          pb[qb][slab][jj] = pku;
-          eb_prev = eb;
-          qb_prev = qb;
-        }
+      for (int j = NEAR + (i * NMAIN + EW - 1) / EW; j < NEAR + ((i + 1) * NMAIN + EW - 1) / EW && j < NE; ++j)
+        exp_event(s_cur, lsum, j, j == NEAR);
+      // ... and, below the causal horizon, the early ones of half hh+1, whose S^T is complete by now
+      if (!MASKED && NEAR > 0 && i >= EW) {
+#pragma unroll
+        for (int j = ((i - EW) * NEAR + (M - EW) - 1) / (M - EW); j < ((i - EW + 1) * NEAR + (M - EW) - 1) / (M - EW) && j < NEAR; ++j)
+          exp_event(s_next, lsum_next, j, j == 0);
+        if (i == M - 1) lsum_next[ev_qb] += ev_b;
       }
-      if (i == EW) lsum[qb_prev] += eb_prev;
       if (SUM_MODE && i == EW + 1) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) sum_flag |= (int)!(lsum[qb] <= kSumThreshold);
@@ -567,12 +600,16 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) l_run[qb] += lsum[qb];
+    for (int qb = 0; qb < QB; ++qb) {
+      l_run[qb] += lsum[qb];
+      lsum_early[qb] = lsum_next[qb];
+    }
     if constexpr (SUM_MODE) {
       if (__builtin_expect(__any(sum_flag), 0)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
         rescale_from_sum(lsum, s_next);
+        if (!MASKED) early_events(s_next);  // they were formed against the old reference: once more
       }
     }
     if (MASKED) {
@@ -587,6 +624,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       for (int qb = 0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
       rescale_apply(dm, s_next);
     }
+    if (MASKED) early_events(s_next);
   };
 
   if (t_begin < t_end) {
@@ -625,6 +663,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
         float mx[QB], dm[QB];
         rowmax_all(sA, mx);
         if (rescale_decide(mx, dm)) rescale_apply(dm, sA);
+        early_events(sA);
         // first K batch of the first step: second half of tile t_begin
 #pragma unroll
         for (int j = 0; j < GK; ++j) kg[0][j] = k_frag(j, HALFB);

@@ -81,28 +81,14 @@ struct Plan {
   int units_per_wave, units_per_head, wgs_per_head, n_splits, tiles_per_split, n_wgs, pair_order;
 };
 
-Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
+// Launch geometry for `upw` units per wavefront: enough prefix splits to put at least `target`
+// workgroups on the chip when the unsplit grid has fewer (a forced split count overrides that).
+Plan plan_with(const kvfold_cache* c, int n_tokens, int64_t len_after, int upw) {
   const kvfold_config_t& f = c->cfg;
   const int G = f.n_q_heads / f.n_kv_heads;
   Plan pl;
-  pl.units_per_head = G * ((n_tokens + kRowsPerUnit - 1) / kRowsPerUnit);
-  int upw = 1;
   pl.pair_order = 0;
-  if (f.dtype == KVFOLD_BF16) {
-    upw = c->tune_units_per_wave ? c->tune_units_per_wave : 2;
-    const int64_t units = (int64_t)f.n_kv_heads * pl.units_per_head;
-    if (!c->tune_units_per_wave) {
-      // two units per wave only pays when there are enough units to keep every CU busy
-      if (units < (int64_t)c->n_cu * kUnitsPerWg * 2) upw = 1;
-      // Short prefix: the causal part makes late token blocks up to twice as long as early ones.  If
-      // the one-unit-per-wave grid is resident at once (two workgroups per CU) pair heavy with light.
-      const int64_t wgs1 = (int64_t)f.n_kv_heads * ((pl.units_per_head + kUnitsPerWg - 1) / kUnitsPerWg);
-      if (len_after < 4 * (int64_t)n_tokens && wgs1 <= 2 * (int64_t)c->n_cu && wgs1 > (int64_t)c->n_cu) {
-        upw = 1;
-        pl.pair_order = 1;
-      }
-    }
-  }
+  pl.units_per_head = G * ((n_tokens + kRowsPerUnit - 1) / kRowsPerUnit);
   pl.units_per_wave = upw;
   const int per_wg = kUnitsPerWg * upw;
   pl.wgs_per_head = (pl.units_per_head + per_wg - 1) / per_wg;
@@ -117,8 +103,24 @@ Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
   if (c->tune_splits > 0) {
     s = c->tune_splits;
   } else {
-    const int64_t target = (int64_t)c->n_cu * (upw == 1 ? 2 : 1);  // resident workgroups on the chip
-    if (base * 4 < target * 3) s = (target + base - 1) / base;      // under 3/4 of a wave of workgroups
+    // Workgroups run in rounds of `slots` (one per CU with two units per wavefront, else two).  Score
+    // a split count by the fill of its last round, a small bonus for more rounds (the dispatcher evens
+    // out unequal workgroups), and the cost of writing and merging s sets of fp32 partials, relative
+    // to the attention work at about 1.1 PFLOP/s and 4 TB/s.
+    const int64_t slots = (int64_t)c->n_cu * (upw == 1 ? 2 : 1);
+    const double flops = 4.0 * f.n_q_heads * f.head_dim * (double)n_tokens * ((double)len_after - 0.5 * n_tokens);
+    const double t_attn = flops / 1.1e15 + 2e-6;
+    double best = -1.0;
+    for (int64_t cand = 1; cand <= s_max; ++cand) {
+      const int64_t w = base * cand, rounds = (w + slots - 1) / slots;
+      const double fill = (double)w / (double)(rounds * slots);
+      const double merge = cand > 1 ? ((double)cand * rows * (f.head_dim + 2) * 8.0 / 4e12 + 4e-6) / t_attn : 0.0;
+      const double score = fill * (1.0 - 0.05 / (double)rounds) / (1.0 + merge);
+      if (score > best * 1.005) {
+        best = score;
+        s = cand;
+      }
+    }
   }
   if (s > s_max) s = s_max;
   pl.tiles_per_split = (int)((ntiles + s - 1) / s);
@@ -126,8 +128,30 @@ Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
   pl.n_splits = (ntiles + pl.tiles_per_split - 1) / pl.tiles_per_split;
   if (pl.n_splits < 1) pl.n_splits = 1;
   pl.n_wgs = (int)(base * pl.n_splits);
-  if (pl.n_splits > 1) pl.pair_order = 0;
   return pl;
+}
+
+Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
+  const kvfold_config_t& f = c->cfg;
+  if (f.dtype != KVFOLD_BF16) return plan_with(c, n_tokens, len_after, 1);
+  if (c->tune_units_per_wave) return plan_with(c, n_tokens, len_after, c->tune_units_per_wave);
+  Plan p1 = plan_with(c, n_tokens, len_after, 1);
+  // Short prefix: the causal part makes late token blocks up to twice as long as early ones.  If the
+  // one-unit-per-wavefront grid is resident at once (two workgroups per CU), pair heavy with light.
+  const int64_t wgs1 = (int64_t)f.n_kv_heads * p1.wgs_per_head;
+  if (c->tune_splits == 0 && len_after < 4 * (int64_t)n_tokens && wgs1 <= 2 * (int64_t)c->n_cu &&
+      wgs1 > (int64_t)c->n_cu && p1.n_splits == 1) {
+    p1.pair_order = 1;
+    return p1;
+  }
+  // Two units per wavefront is the faster kernel (every LDS fragment feeds two MFMAs) whenever it
+  // can fill the chip, if need be by splitting the prefix; one unit per wavefront is for grids too
+  // small for that, and for chunks so short that half of the two-unit workgroup would idle.
+  const Plan p2 = plan_with(c, n_tokens, len_after, 2);
+  const int64_t padded1 = (int64_t)p1.wgs_per_head * kUnitsPerWg, padded2 = (int64_t)p2.wgs_per_head * kUnitsPerWg * 2;
+  if (padded2 * 5 > padded1 * 6) return p1;                                   // more than 20 % extra padding
+  if ((int64_t)p2.n_wgs * 4 < (int64_t)c->n_cu * 3 && p1.n_wgs > p2.n_wgs) return p1;  // cannot fill the chip
+  return p2;
 }
 
 struct DeviceGuard {
