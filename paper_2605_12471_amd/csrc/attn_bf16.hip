@@ -82,14 +82,15 @@ __device__ __forceinline__ void wait_vm() {
 }
 
 // MFMA issued by hand so that the register files are under control: S^T accumulates in VGPRs
-// (the vector ALU reads it next), O^T in AGPRs, and the Q fragments sit in AGPRs as B operands.
+// (the vector ALU reads it next), O^T in AGPRs, and the Q fragments (B operands) and the K
+// fragments (A operands, loaded from LDS straight into AGPRs) sit in AGPRs too.
 // The compiler does not see these as matrix instructions, so the read-after-MFMA-write distances
 // the hardware needs are kept by construction (see mfma_settle_*()).
 __device__ __forceinline__ void mfma_qk_first(floatx16& s, const bf16x8& a, const bf16x8& q, const floatx16& c0) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(s) : "v"(a), "a"(q), "v"(c0));
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(s) : "a"(a), "a"(q), "v"(c0));
 }
 __device__ __forceinline__ void mfma_qk(floatx16& s, const bf16x8& a, const bf16x8& q) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(a), "a"(q));
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "a"(a), "a"(q));
 }
 __device__ __forceinline__ void mfma_pv(floatx16& o, const bf16x8& a, const bf16x8& pfrag) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o) : "v"(a), "v"(pfrag));
@@ -219,13 +220,16 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     const unsigned lds = lds0 + (unsigned)(((is_v ? NK : 0) + slot) * TILEB + (w + 4 * i) * 1024);
     unsigned off;
     if (CLAMP) {
-      unsigned grow = (unsigned)(t * BN + dma_row0 + i * 4 * RPS);
-      grow = (grow < (unsigned)Lm1 ? grow : (unsigned)Lm1) + extra;
-      off = grow * ROWB + (is_v ? dma_vc : dma_kc);
+      int row0_here = dma_row0;  // opaque copy: what is derived from it is computed here, not once ahead of all
+      asm volatile("" : "+v"(row0_here));  // loops and then held in registers through the main loop
+      unsigned grow = (unsigned)(t * BN + row0_here + i * 4 * RPS);
+      grow = grow < (unsigned)Lm1 ? grow : (unsigned)Lm1;
+      off = grow * ROWB + (is_v ? dma_vc : dma_kc) + extra;
+      dma16(is_v ? vbase : kbase, off, lds);
     } else {
       off = (is_v ? dma_voff : dma_koff) + (unsigned)(t * BN + i * 4 * RPS) * ROWB;
+      dma16(is_v ? vbase : kbase, off, lds);
     }
-    dma16(is_v ? vbase : kbase, off, lds);
   };
   auto issue_k = [&](int t, unsigned extra) __attribute__((always_inline)) {
 #pragma unroll
@@ -280,8 +284,16 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   };
 
   // ---- building blocks of the software pipeline --------------------------------------------
+  // K fragment ks of the current K tile (imm = 0) or of its second half (imm = HALFB), read from LDS
+  // straight into AGPRs.  The compiler does not see an LDS access here: every use is covered by one
+  // of the wait_lds<>() calls of the pipeline.
   auto k_frag = [&](int ks, int imm) __attribute__((always_inline)) -> bf16x8 {
-    return *LDS_PTR(const bf16x8, kaddr[ks] + (unsigned)imm);
+    bf16x8 f;
+    if (imm == 0)
+      asm volatile("ds_read_b128 %0, %1" : "=a"(f) : "v"(kaddr[ks]));
+    else
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=a"(f) : "v"(kaddr[ks]), "n"(HALFB));
+    return f;
   };
   auto v_frag = [&](int tt, int db, int imm) __attribute__((always_inline)) -> bf16x8 {
     const unsigned a0 = vaddr[db] + (unsigned)(imm + 16 * tt * ROWB);
@@ -292,13 +304,19 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   };
   // causal mask of the 32-key half hh
   auto mask_half = [&](floatx16 (&s)[QB], int hh) __attribute__((always_inline)) {
+    // (opaque copies: whatever is derived from them is computed here, not once ahead of all loops and
+    // then held in registers through the unmasked main loop)
+    int hi_here = hi;
+    asm volatile("" : "+v"(hi_here));
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       if (hh * 32 + 32 > vis_first[qb]) {  // wave-uniform
-        const int rel = my_vis[qb] - hh * 32;
+        int vis_here = my_vis[qb];
+        asm volatile("" : "+v"(vis_here));
+        const int rel = vis_here - hh * 32;
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          if (8 * (r >> 2) + 4 * hi + (r & 3) >= rel) s[qb][r] = -INFINITY;
+          if (8 * (r >> 2) + 4 * hi_here + (r & 3) >= rel) s[qb][r] = -INFINITY;
       }
     }
   };
@@ -647,14 +665,16 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       __builtin_amdgcn_s_barrier();
       {
 #pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kg[ks / GK][ks % GK] = k_frag(ks, 0);
+        wait_lds<0>();
+#pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 a = k_frag(ks, 0);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) {
             if (ks == 0)
-              mfma_qk_first(sA[qb], a, qf[qb][ks], negm[qb]);
+              mfma_qk_first(sA[qb], kg[0][0], qf[qb][ks], negm[qb]);
             else
-              mfma_qk(sA[qb], a, qf[qb][ks]);
+              mfma_qk(sA[qb], kg[ks / GK][ks % GK], qf[qb][ks]);
           }
         }
 #pragma unroll
