@@ -3,28 +3,58 @@
 // different workgroups; each leaves, per (row, head), its running maximum m_s (log2 units), the
 // sum l_s of 2^(logit - m_s) and the unnormalised O_s.  Softmax over the union is recovered exactly:
 //   M = max_s m_s,  L = sum_s l_s 2^(m_s - M),  out = sum_s O_s 2^(m_s - M) / L.
-// HBM-bound (reads S * (d + 2) floats per row once, writes d elements).
+// HBM-bound (reads S * (d + 2) floats per row once, writes d elements); launch-latency bound for few rows.
 #include "kvfold_internal.h"
 
 namespace kvfold {
 
-__global__ void __launch_bounds__(256) combine_kernel(CombineParams p) {
-  const int vec_per_row = p.head_dim >> 2;
-  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t row = gid / vec_per_row;
-  const int dv = (int)(gid - row * vec_per_row);
-  if (row >= p.n_rows) return;
+// Thread layout of a 256-thread block: rows_per_block rows x SG split groups x V 16-byte column
+// vectors (V = head_dim / 4).  Split group sg of a row folds pieces sg, sg + SG, ... into one running
+// (m, l, O); the SG results meet in LDS.  With few rows (decode-shaped steps: 32 rows, 64 pieces) this
+// keeps every load of a row in flight at once instead of walking the pieces one after another.
+constexpr int kCombineThreads = 256;
+
+__global__ void __launch_bounds__(kCombineThreads) combine_kernel(CombineParams p, int SG, int rows_per_block) {
+  extern __shared__ float4 red[];  // [rows_per_block][SG][V] partial O, then [rows_per_block][SG] (m, l) pairs
+  const int V = p.head_dim >> 2;
+  const int tid = threadIdx.x;
+  const int dv = tid % V, sg = (tid / V) % SG, rl = tid / (V * SG);
+  const int64_t row = (int64_t)blockIdx.x * rows_per_block + rl;
+  const bool live = rl < rows_per_block && row < p.n_rows;
+  float2* red_ml = reinterpret_cast<float2*>(red + rows_per_block * SG * V);
+
+  float m = -INFINITY, l = 0.f;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (live) {
+    for (int s = sg; s < p.n_splits; s += SG) {
+      const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + ((int64_t)s * p.n_rows + row) * 2);
+      const float4 o = *reinterpret_cast<const float4*>(p.part_o + ((int64_t)s * p.n_rows + row) * p.head_dim + dv * 4);
+      if (ml.y == 0.f) continue;  // this piece saw no visible key for the row
+      const float mn = fmaxf(m, ml.x);
+      const float a = exp2f(m - mn), b = exp2f(ml.x - mn);  // m = -inf the first time: a = 0
+      l = l * a + ml.y * b;
+      acc.x = acc.x * a + o.x * b;
+      acc.y = acc.y * a + o.y * b;
+      acc.z = acc.z * a + o.z * b;
+      acc.w = acc.w * a + o.w * b;
+      m = mn;
+    }
+    red[(rl * SG + sg) * V + dv] = acc;
+    if (dv == 0) red_ml[rl * SG + sg] = make_float2(m, l);
+  }
+  __syncthreads();
+  if (!live || sg != 0) return;
 
   float M = -INFINITY;
-  for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, p.part_ml[((int64_t)s * p.n_rows + row) * 2]);
+  for (int g = 0; g < SG; ++g) M = fmaxf(M, red_ml[rl * SG + g].x);
   float Lsum = 0.f;
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int s = 0; s < p.n_splits; ++s) {
-    const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + ((int64_t)s * p.n_rows + row) * 2);
-    if (ml.y == 0.f) continue;  // this piece saw no visible key for the row
+  acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int g = 0; g < SG; ++g) {
+    const float2 ml = red_ml[rl * SG + g];
+    if (ml.y == 0.f) continue;
     const float wgt = exp2f(ml.x - M);
     Lsum += wgt * ml.y;
-    const float4 o = *reinterpret_cast<const float4*>(p.part_o + ((int64_t)s * p.n_rows + row) * p.head_dim + dv * 4);
+    const float4 o = red[(rl * SG + g) * V + dv];
     acc.x += wgt * o.x;
     acc.y += wgt * o.y;
     acc.z += wgt * o.z;
@@ -48,9 +78,18 @@ __global__ void __launch_bounds__(256) combine_kernel(CombineParams p) {
 }
 
 hipError_t launch_combine(const CombineParams& p, hipStream_t s) {
-  const int64_t threads = (int64_t)p.n_rows * (p.head_dim >> 2);
-  if (threads <= 0) return hipSuccess;
-  hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p);
+  if (p.n_rows <= 0) return hipSuccess;
+  const int V = p.head_dim >> 2;  // 16 or 32
+  // Split groups (a power of two, at most the number of pieces and what one row's share of a block
+  // allows) only as far as they are needed to put about two blocks on every CU: with many rows one
+  // thread per (row, column vector) walking the pieces is the cheaper form.
+  const int64_t blocks1 = ((int64_t)p.n_rows * V + kCombineThreads - 1) / kCombineThreads;
+  int SG = 1;
+  while (SG < p.n_splits && SG * 2 * V <= kCombineThreads && blocks1 * SG < 512) SG *= 2;
+  const int rows_per_block = kCombineThreads / (V * SG);
+  const unsigned blocks = (unsigned)((p.n_rows + rows_per_block - 1) / rows_per_block);
+  const size_t lds = (size_t)rows_per_block * SG * (V * sizeof(float4) + sizeof(float2));
+  hipLaunchKernelGGL(combine_kernel, dim3(blocks), dim3(kCombineThreads), lds, s, p, SG, rows_per_block);
   return hipGetLastError();
 }
 

@@ -74,7 +74,7 @@ size_t bytes_required(const kvfold_config_t* c) {
 }
 
 constexpr int64_t kMaxSplitRows = 1 << 18;  // cap on S * C * Hq rows held in the split workspace
-constexpr int kMaxSplits = 32;
+constexpr int kMaxSplits = 64;
 constexpr int kMinTilesPerSplit = 8;
 
 struct Plan {
