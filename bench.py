@@ -151,6 +151,49 @@ def cpu_baseline(w, torch):
     }
 
 
+def decode_shaped_points(torch, kv, I, dev, L=131072, chunks=(1, 4, 16), reps=20):
+    """Fold steps of 1..16 tokens against a 128K cache of the Llama-shaped layer (the greedy decode
+    that follows the chain in the needle protocol, Sec. 4): HBM-bound, reported against the 8 TB/s
+    peak.  The cache rows are seeded N(0,1) written in place; each step is timed with the library's
+    HIP events (append, attention, merge) over `reps` repeats against the rewound cache."""
+    cfg = I.CONFIGS["llama_16k"]
+    pts = []
+    for C in chunks:
+        Lp = L - C
+        cache = kv.KvFoldCache(1, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, C, L, "bf16", device=dev.index or 0)
+        g = torch.Generator(device=dev)
+        g.manual_seed(I.BASE_SEED + C)
+        K, V = cache.view(0)
+        K.normal_(generator=g)
+        V.normal_(generator=g)
+        q, k, v = (torch.randn((C, h, cfg.head_dim), device=dev, generator=g).bfloat16()
+                   for h in (cfg.n_q_heads, cfg.n_kv_heads, cfg.n_kv_heads))
+        out = torch.empty_like(q)
+        for _ in range(3):
+            cache.set_length(0, Lp)
+            cache.step(0, q, k, v, out, pos_offset=Lp)
+        torch.cuda.synchronize()
+        cache.profile_begin(reps)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            cache.set_length(0, Lp)
+            cache.step(0, q, k, v, out, pos_offset=Lp)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / reps
+        n, a_ms, t_ms, m_ms = cache.profile_end()
+        nbytes = step_bytes(cfg, C, Lp)
+        pts.append({
+            "C": C, "L_prev": Lp, "plan_workgroups_splits": list(cache.plan(C, L)),
+            "step_ms": wall_ms, "append_ms": a_ms / n, "attention_ms": t_ms / n, "merge_ms": m_ms / n,
+            "tokens_per_s": C / (wall_ms * 1e-3), "algorithmic_bytes": nbytes,
+            "roofline": {"kernel": "attn_bf16_kernel", "bound": "hbm", "achieved": nbytes / (t_ms / n * 1e-3) / 1e9,
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": nbytes / (t_ms / n * 1e-3) / 1e9 / PEAK_HBM_GBS},
+            "step_GBps": nbytes / (wall_ms * 1e-3) / 1e9,
+        })
+        cache.close()
+    return pts
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -252,6 +295,7 @@ def main():
                            "algorithmic_GBps": step_bytes(c2, c2.chunk, L) / (t * 1e-3) / 1e9} for L, t in sel],
             }
             w2.close()
+        extra["decode_shaped_128k"] = decode_shaped_points(torch, kv, I, dev)
     result["extra"] = extra
     print(json.dumps(result))
 

@@ -154,3 +154,34 @@ def test_config5_chunk_size_and_precision_sweep(H, oracle):
         report[f"fp32 vs bf16 C={C}"] = d
         assert d <= 6e-2   # input rounding of q, k, v to bf16 dominates
     print("config 5 drift report", report)
+
+
+@pytest.mark.parametrize("C", [1, 4, 16])
+def test_decode_shaped_steps_against_128k_cache(H, oracle, C):
+    """Steps of 1..16 tokens against a 128K cache of the Llama-shaped layer (the decode that follows the
+    chain, Sec. 4): 64 prefix splits + merge, every row and head against the oracle, cache bit-exact."""
+    L = 131072
+    cfg = I.CONFIGS["llama_16k"].with_(name="decode_128k", config_id=6, chunk=C, total_tokens=L)
+    Lp = L - C
+    gpu = H.GpuFold(cfg, capacity=L, chunk_tokens=C)
+    oc = H.make_oracle(oracle, cfg, capacity=L)
+    try:
+        kd, vd = gpu.cache.view(0)                       # [Hkv][capacity][d]
+        for t0 in range(0, Lp, 16384):                   # prefix rows: the seeded token stream, written in place
+            n = min(16384, Lp - t0)
+            _, k, v = I.chunk_qkv(cfg, 0, 0, n_tokens=n, token_base=t0)
+            oc.append(H.bits(k), H.bits(v))
+            kd[:, t0:t0 + n].copy_(k.to(DEV).transpose(0, 1))
+            vd[:, t0:t0 + n].copy_(v.to(DEV).transpose(0, 1))
+        gpu.cache.set_length(0, Lp)
+        assert gpu.cache.plan(C, L)[1] > 1               # the prefix is split
+        q, k, v = I.chunk_qkv(cfg, 0, 0, n_tokens=C, token_base=Lp)
+        out, lse = gpu.step(0, q, k, v, want_lse=True)
+        ref, ref_lse = H.oracle_step(oc, q, k, v)
+        err = float(np.abs(H.wide(out) - ref).max())
+        assert err <= H.TOL["bf16"], f"C={C}: max|out-oracle| = {err}"
+        assert np.abs(lse.cpu().double().numpy().T - ref_lse).max() <= 2e-2
+        H.assert_cache_bit_exact(gpu, oc)
+        print(f"decode-shaped C={C}: max-abs error {err}")
+    finally:
+        gpu.close()
