@@ -116,6 +116,40 @@ int kvfold_oracle_attend_rows(const double *Kc, const double *Vc, int64_t Hkv,
     return fail ? -3 : 0;
 }
 
+/*
+ * Rotary position embedding of the new tokens at their absolute positions (Sec. 2, "KV-Fold":
+ * position identifiers of chunk t continue from tC, so the rotations are aligned with the original
+ * sequence).  x: [rows][heads][d] fp32, row i belongs to position pos_offset + i; the caller passes
+ * the angles of exactly those positions, cos/sin: [rows][d/2] fp32 (a model's rotary cache).
+ * Pairing (the paper is silent; the reading taken is the half-split layout of the Llama family):
+ * element j pairs with element j + d/2,
+ *     out_j       = x_j cos_j - x_{j+d/2} sin_j
+ *     out_{j+d/2} = x_{j+d/2} cos_j + x_j sin_j.
+ * Precision: the product layer rotates in fp32 and stores the mode dtype, so this is the one place
+ * where the oracle works in fp32 too, with the rounding points fixed: the subtrahend / addend
+ * product is rounded to fp32, then one fused multiply-add.
+ */
+int kvfold_oracle_rope_f32(const float *x, int64_t rows, int64_t heads, int64_t d,
+                           const float *cosv, const float *sinv, float *out)
+{
+    if (d % 2) return -1;
+    const int64_t hd = d / 2;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t h = 0; h < heads; ++h) {
+            const float *xi = x + ((size_t)i * heads + h) * d;
+            float *oi = out + ((size_t)i * heads + h) * d;
+            for (int64_t j = 0; j < hd; ++j) {
+                const float c = cosv[(size_t)i * hd + j], s = sinv[(size_t)i * hd + j];
+                const float lo = xi[j], hi = xi[j + hd];
+                const float t0 = hi * s;      /* rounded to fp32 */
+                const float t1 = lo * s;
+                oi[j] = fmaf(lo, c, -t0);
+                oi[j + hd] = fmaf(hi, c, t1);
+            }
+        }
+    return 0;
+}
+
 int kvfold_oracle_threads(void)
 {
 #ifdef _OPENMP

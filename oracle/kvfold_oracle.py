@@ -19,7 +19,8 @@ What it holds
 Readings of the paper taken here (the paper is silent on all of them):
 contiguous grouped-query mapping (query head h -> KV head h // (Hq/Hkv)),
 diagonal-inclusive causal mask, softmax scale 1/sqrt(d) unless given,
-queries/keys used as handed in (already rotated).
+queries/keys used as handed in (already rotated); :func:`rope` is the rotation
+itself for the entry point that takes them unrotated (half-split pairing, fp32).
 
 Parity pins: tests/test_oracle_pins.py (fold invariant vs the monolithic pass,
 brute-force python loops, torch's fp64 scaled_dot_product_attention, closed
@@ -63,6 +64,8 @@ def _load():
                                                       ctypes.c_double, vp, i64, vp, vp, vp]
             lib.kvfold_oracle_attend_rows.restype = ctypes.c_int
             lib.kvfold_oracle_threads.restype = ctypes.c_int
+            lib.kvfold_oracle_rope_f32.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+            lib.kvfold_oracle_rope_f32.restype = ctypes.c_int
             _lib = lib
     return _lib
 
@@ -74,6 +77,33 @@ def threads() -> int:
 
 def _ptr(a: np.ndarray):
     return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even of fp32 values to bfloat16 bit patterns (finite values and infinities)."""
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def rope(x: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
+    """Rotary embedding of x [rows][heads][d] (fp32) by the angles cos/sin [rows][d/2] of the rows'
+    absolute positions (Sec. 2: positions continue from tC), half-split pairing, fp32 with the
+    rounding points of ``kvfold_oracle_rope_f32``.  Returns fp32; a bf16 fold stores
+    ``f32_to_bf16_bits`` of it."""
+    x = np.ascontiguousarray(x, np.float32)
+    rows, heads, d = x.shape
+    cos = np.ascontiguousarray(cos, np.float32)
+    sin = np.ascontiguousarray(sin, np.float32)
+    assert cos.shape == (rows, d // 2) and sin.shape == (rows, d // 2)
+    out = np.empty_like(x)
+    rc = _load().kvfold_oracle_rope_f32(_ptr(x), rows, heads, d, _ptr(cos), _ptr(sin), _ptr(out))
+    if rc:
+        raise ValueError("head_dim must be even")
+    return out
 
 
 class OracleCache:

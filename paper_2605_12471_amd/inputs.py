@@ -146,6 +146,16 @@ def steered_qkv(cfg: FoldConfig, layer: int, step: int, profile: str, device="cp
     return q, k, v
 
 
+def rope_tables(head_dim: int, pos0: int, n_tokens: int, theta: float = 500000.0, device="cpu"):
+    """cos / sin [n_tokens][head_dim/2] fp32 of the angles (pos0 + i) * theta^(-2j/head_dim): what a model's
+    rotary cache holds for the absolute positions of one chunk (theta = 500000 is the Llama-3 base).
+    Angles are formed in fp64 and rounded once."""
+    j = torch.arange(head_dim // 2, dtype=torch.float64)
+    inv_freq = theta ** (-2.0 * j / head_dim)
+    ang = torch.arange(pos0, pos0 + n_tokens, dtype=torch.float64)[:, None] * inv_freq[None, :]
+    return ang.cos().float().to(device).contiguous(), ang.sin().float().to(device).contiguous()
+
+
 @dataclasses.dataclass(frozen=True)
 class NeedleSpec:
     key_pos: int      # absolute token position of the planted key (inside chunk 0)

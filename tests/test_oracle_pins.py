@@ -285,3 +285,74 @@ def test_steered_inputs_have_the_stated_logits():
         s = np.einsum("ihx,jgx->ihgj", q.double().numpy(), k.double().numpy()) / np.sqrt(128.0)
         want = np.array([fn(j) for j in range(256)])
         assert np.abs(s - want[None, None, None, :]).max() < 0.8 + 0.02 * want.max(), profile
+
+
+# ---- rotary embedding of the new tokens at absolute positions (Sec. 2: positions continue from tC)
+
+def _angles(rows, hd, seed, pos0=0):
+    rng = np.random.default_rng(seed)
+    inv = 10000.0 ** (-np.arange(hd) / hd)
+    ang = (pos0 + np.arange(rows))[:, None] * inv[None, :]
+    return ang, rng
+
+
+def test_rope_is_a_complex_rotation_of_the_half_split_pairs(oracle):
+    """Element j and j + d/2 form the complex number x_j + i x_{j+d/2}; the rotation is multiplication by
+    e^{i angle}.  Checked against numpy's complex128 arithmetic (an independent formula) to fp32 accuracy."""
+    rows, heads, d = 37, 3, 64
+    ang, rng = _angles(rows, d // 2, 1, pos0=1000)
+    x = rng.standard_normal((rows, heads, d)).astype(np.float32)
+    got = oracle.rope(x, np.cos(ang), np.sin(ang)).astype(np.float64)
+    z = (x[..., : d // 2] + 1j * x[..., d // 2:]) * np.exp(1j * ang)[:, None, :]
+    want = np.concatenate([z.real, z.imag], axis=-1)
+    assert np.abs(got - want).max() < 5e-7 * np.abs(x).max() * 2
+
+
+def test_rope_special_angles_are_exact(oracle):
+    rows, heads, d = 5, 2, 16
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((rows, heads, d)).astype(np.float32)
+    one, zero = np.ones((rows, d // 2), np.float32), np.zeros((rows, d // 2), np.float32)
+    assert np.array_equal(oracle.rope(x, one, zero), x)                       # angle 0: identity (position 0)
+    quarter = oracle.rope(x, zero, one)                                       # angle pi/2: (a, b) -> (-b, a)
+    assert np.array_equal(quarter[..., : d // 2], -x[..., d // 2:]) and np.array_equal(quarter[..., d // 2:], x[..., : d // 2])
+    assert np.array_equal(oracle.rope(x, -one, zero), -x)                     # angle pi
+
+
+def test_rope_keeps_norms_and_makes_logits_depend_on_relative_position(oracle):
+    """|R x| = |x|, and (R_m q).(R_n k) = (R_{m-n} q).k: the property that makes continued absolute
+    positions across chunk boundaries equivalent to one long sequence."""
+    heads, d = 2, 64
+    rng = np.random.default_rng(3)
+    q = rng.standard_normal((1, heads, d)).astype(np.float32)
+    k = rng.standard_normal((1, heads, d)).astype(np.float32)
+    inv = 10000.0 ** (-np.arange(d // 2) / (d // 2))
+
+    def rot(x, pos):
+        a = (pos * inv)[None, :]
+        return oracle.rope(x, np.cos(a), np.sin(a)).astype(np.float64)
+
+    for m, n in ((5, 3), (4099, 4096), (131071, 131000), (17, 17)):
+        qm, kn = rot(q, m), rot(k, n)
+        assert abs(np.linalg.norm(qm) - np.linalg.norm(q.astype(np.float64))) < 1e-5
+        lhs = (qm * kn).sum(-1)
+        rhs = (rot(q, m - n) * k.astype(np.float64)).sum(-1)
+        assert np.abs(lhs - rhs).max() < 2e-4, (m, n)
+
+
+def test_bf16_rounding_helper_is_round_to_nearest_even(oracle):
+    """f32_to_bf16_bits against torch's own conversion on random values, ties and the largest finite value."""
+    import torch
+    rng = np.random.default_rng(4)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * 10.0 ** rng.integers(-20, 20, 20000),
+                        np.array([1.00390625, 1.01171875, -1.00390625, 0.0, -0.0, 3.3895314e38, np.inf, -np.inf], np.float32)])
+    want = torch.from_numpy(x).bfloat16().view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(oracle.f32_to_bf16_bits(x), want)
+    assert np.array_equal(oracle.bf16_bits_to_f32(want), torch.from_numpy(x).bfloat16().float().numpy())
+
+
+def test_rope_tables_generator_matches_its_formula():
+    from paper_2605_12471_amd import inputs as I
+    cos, sin = I.rope_tables(8, 100, 3, theta=10000.0)
+    ang = np.arange(100, 103)[:, None] * 10000.0 ** (-2.0 * np.arange(4) / 8)[None, :]
+    assert np.allclose(cos.numpy(), np.cos(ang), atol=1e-7) and np.allclose(sin.numpy(), np.sin(ang), atol=1e-7)
