@@ -118,6 +118,30 @@ int kvfold_step_ex(kvfold_cache_t* cache, int layer, const void* q, const void* 
                    int32_t n_tokens, int64_t pos_offset, void* out, float* lse, void* stream);
 
 /*
+ * Same step for callers that hold q and k_new UNROTATED: the rotary position
+ * embedding of the new tokens at their absolute positions pos_offset + i is
+ * applied inside the step ("Position identifiers for the new tokens are
+ * continued from the absolute sequence position", Sec. 2) -- to the K rows as
+ * they are appended (the cache holds rotated keys, as a model's cache does) and
+ * to the queries as the attention kernel loads them; V is untouched.
+ *   rope_cos, rope_sin  device, [n_tokens][head_dim/2] float, 16-byte aligned:
+ *        cosine and sine of the angle of pair j at row i's absolute position
+ *        (what a model's rotary cache holds for positions pos_offset ..
+ *        pos_offset + n_tokens - 1; frequencies and any scaling are the
+ *        caller's).  Both required, else KVFOLD_ERR_INVALID_ARG.
+ * Pairing is the half-split layout of the Llama family: element j rotates with
+ * element j + head_dim/2,
+ *        x'_j = x_j cos_j - x_{j+d/2} sin_j,  x'_{j+d/2} = x_{j+d/2} cos_j + x_j sin_j,
+ * in fp32 (the product with the sine rounded first, then one fused multiply-
+ * add) and rounded to the mode's element type.  The result is bit for bit
+ * what kvfold_step_ex returns, and leaves in the cache, for inputs rotated that
+ * way beforehand.  All other arguments, layouts and errors as kvfold_step_ex.
+ */
+int kvfold_step_rope(kvfold_cache_t* cache, int layer, const void* q, const void* k_new, const void* v_new,
+                     int32_t n_tokens, int64_t pos_offset, const float* rope_cos, const float* rope_sin, void* out,
+                     float* lse, void* stream);
+
+/*
  * Destroy a cache: synchronises the device, frees library-owned memory (never
  * a caller-provided kv_buffer).  NULL is a no-op returning KVFOLD_OK.
  */

@@ -67,6 +67,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvfold_step.restype = ctypes.c_int
     lib.kvfold_step_ex.argtypes = [vp, ctypes.c_int, vp, vp, vp, i32, i64, vp, vp, vp]
     lib.kvfold_step_ex.restype = ctypes.c_int
+    lib.kvfold_step_rope.argtypes = [vp, ctypes.c_int, vp, vp, vp, i32, i64, vp, vp, vp, vp, vp]
+    lib.kvfold_step_rope.restype = ctypes.c_int
     lib.kvfold_cache_destroy.argtypes = [vp]
     lib.kvfold_cache_destroy.restype = ctypes.c_int
     lib.kvfold_cache_length.argtypes = [vp, ctypes.c_int]
@@ -122,6 +124,12 @@ def kvfold_step(cache, layer, q, k_new, v_new, pos_offset, out, stream=0) -> int
 
 def kvfold_step_ex(cache, layer, q, k_new, v_new, n_tokens, pos_offset, out, lse=None, stream=0) -> int:
     return load_library().kvfold_step_ex(cache, layer, q, k_new, v_new, n_tokens, pos_offset, out, lse, stream)
+
+
+def kvfold_step_rope(cache, layer, q, k_new, v_new, n_tokens, pos_offset, rope_cos, rope_sin, out, lse=None,
+                     stream=0) -> int:
+    return load_library().kvfold_step_rope(cache, layer, q, k_new, v_new, n_tokens, pos_offset, rope_cos, rope_sin,
+                                           out, lse, stream)
 
 
 def kvfold_cache_destroy(cache) -> int:
@@ -221,16 +229,28 @@ class KvFoldCache:
         import torch
         return torch.cuda.current_stream().cuda_stream
 
-    def step(self, layer, q, k_new, v_new, out, pos_offset=None, lse=None, stream=None):
-        """Enqueue one fold step; q/k_new/v_new/out (and lse) are contiguous device tensors."""
+    def step(self, layer, q, k_new, v_new, out, pos_offset=None, lse=None, stream=None, rope=None):
+        """Enqueue one fold step; q/k_new/v_new/out (and lse) are contiguous device tensors.  rope = (cos, sin),
+        fp32 device tensors [n][head_dim/2]: q and k_new are unrotated and the step rotates them."""
         n = q.shape[0]
         pos = self.length(layer) if pos_offset is None else pos_offset
         for t in (q, k_new, v_new, out):
             assert t.is_cuda and t.is_contiguous()
-        rc = kvfold_step_ex(self.handle, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), n, pos,
-                            out.data_ptr(), lse.data_ptr() if lse is not None else None, self._stream(stream))
+        lse_ptr = lse.data_ptr() if lse is not None else None
+        if rope is None:
+            rc = kvfold_step_ex(self.handle, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), n, pos,
+                                out.data_ptr(), lse_ptr, self._stream(stream))
+            if rc:
+                raise KvFoldError(rc, "kvfold_step_ex")
+            return out
+        cos, sin = rope
+        for t in (cos, sin):
+            assert t.is_cuda and t.is_contiguous() and t.dtype.is_floating_point and t.element_size() == 4
+            assert tuple(t.shape) == (n, q.shape[-1] // 2)
+        rc = kvfold_step_rope(self.handle, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), n, pos,
+                              cos.data_ptr(), sin.data_ptr(), out.data_ptr(), lse_ptr, self._stream(stream))
         if rc:
-            raise KvFoldError(rc, "kvfold_step_ex")
+            raise KvFoldError(rc, "kvfold_step_rope")
         return out
 
     def length(self, layer=0) -> int:

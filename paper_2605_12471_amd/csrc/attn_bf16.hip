@@ -180,7 +180,22 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ((int64_t)tokc * Hq + head[qb]) * D;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + hi * 8);
+      bf16x8 raw = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + hi * 8);
+      if (p.rope_cos) {
+        // Rotary embedding at the row's absolute position (Sec. 2), half-split pairs (j, j + D/2), fp32 with
+        // the sine product rounded first, result rounded to bf16: bit for bit what a caller that rotates q
+        // itself and stores it as bf16 would hand in.
+        const bool lower = ks < KS / 2;
+        const int j0 = (lower ? ks : ks - KS / 2) * 16 + hi * 8;  // index of the pair's angle
+        const bf16x8 other = *reinterpret_cast<const bf16x8*>(qrow + (lower ? D / 2 : 0) + j0);
+        const float* cs = p.rope_cos + (int64_t)tokc * (D / 2) + j0;
+        const float* sn = p.rope_sin + (int64_t)tokc * (D / 2) + j0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float t = (float)other[e] * sn[e];
+          raw[e] = (__bf16)__builtin_fmaf((float)raw[e], cs[e], lower ? -t : t);
+        }
+      }
 #pragma unroll
       for (int e = 0; e < 8; ++e) qf[qb][ks][e] = (__bf16)((float)raw[e] * sc);
       asm volatile("" : "+a"(qf[qb][ks]));  // park the fragment in the AGPR file, where the MFMAs read it

@@ -69,7 +69,24 @@ __global__ void __launch_bounds__(256, 1) attn_f32_kernel(AttnParams p) {
   {
     const float* qrow = reinterpret_cast<const float*>(p.q) + ((int64_t)tokc * Hq + head) * D;
 #pragma unroll
-    for (int s8 = 0; s8 < D / 8; ++s8) qf[s8] = *reinterpret_cast<const float4*>(qrow + s8 * 8 + hi * 4);
+    for (int s8 = 0; s8 < D / 8; ++s8) {
+      float4 v = *reinterpret_cast<const float4*>(qrow + s8 * 8 + hi * 4);
+      if (p.rope_cos) {
+        // Rotary embedding at the row's absolute position (Sec. 2), half-split pairs (j, j + D/2): the sine
+        // product rounded first, then one fused multiply-add
+        const bool lower = s8 < D / 16;
+        const int j0 = (lower ? s8 : s8 - D / 16) * 8 + hi * 4;  // index of the pair's angle
+        const float4 o = *reinterpret_cast<const float4*>(qrow + (lower ? D / 2 : 0) + j0);
+        const float4 cs = *reinterpret_cast<const float4*>(p.rope_cos + (int64_t)tokc * (D / 2) + j0);
+        const float4 sn = *reinterpret_cast<const float4*>(p.rope_sin + (int64_t)tokc * (D / 2) + j0);
+        const float tx = o.x * sn.x, ty = o.y * sn.y, tz = o.z * sn.z, tw = o.w * sn.w;
+        v.x = __builtin_fmaf(v.x, cs.x, lower ? -tx : tx);
+        v.y = __builtin_fmaf(v.y, cs.y, lower ? -ty : ty);
+        v.z = __builtin_fmaf(v.z, cs.z, lower ? -tz : tz);
+        v.w = __builtin_fmaf(v.w, cs.w, lower ? -tw : tw);
+      }
+      qf[s8] = v;
+    }
   }
 
   int64_t nkeys_wg;

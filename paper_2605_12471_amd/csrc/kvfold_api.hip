@@ -253,8 +253,13 @@ int kvfold_cache_create(const kvfold_config_t* cfg, kvfold_cache_t** out_cache) 
   return KVFOLD_OK;
 }
 
-int kvfold_step_ex(kvfold_cache_t* c, int layer, const void* q, const void* k_new, const void* v_new,
-                   int32_t n_tokens, int64_t pos_offset, void* out, float* lse, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// One fold step; rope_cos / rope_sin both null (inputs used as handed in) or both set.
+int step_impl(kvfold_cache_t* c, int layer, const void* q, const void* k_new, const void* v_new, int32_t n_tokens,
+              int64_t pos_offset, const float* rope_cos, const float* rope_sin, void* out, float* lse, void* stream) {
   if (!c || !q || !k_new || !v_new || !out) return KVFOLD_ERR_INVALID_ARG;
   const kvfold_config_t& f = c->cfg;
   if (layer < 0 || layer >= f.n_layers) return KVFOLD_ERR_BAD_LAYER;
@@ -284,6 +289,9 @@ int kvfold_step_ex(kvfold_cache_t* c, int layer, const void* q, const void* k_ne
   ap.row_bytes = f.head_dim * c->elem_bytes;
   ap.capacity = f.capacity_tokens;
   ap.len_prev = len_prev;
+  ap.rope_cos = rope_cos;
+  ap.rope_sin = rope_sin;
+  ap.elem_is_bf16 = f.dtype == KVFOLD_BF16;
 
   const Plan pl = make_plan(c, n_tokens, len_prev + n_tokens);
   AttnParams at;
@@ -307,6 +315,8 @@ int kvfold_step_ex(kvfold_cache_t* c, int layer, const void* q, const void* k_ne
   at.n_wgs = pl.n_wgs;
   at.pair_order = pl.pair_order;
   at.scale_log2e = c->scale * 1.4426950408889634f;
+  at.rope_cos = rope_cos;
+  at.rope_sin = rope_sin;
   if (pl.n_splits > 1 && (int64_t)pl.n_splits * n_tokens * f.n_q_heads > c->ws_rows) return KVFOLD_ERR_HIP;  // planner bug guard
 
   hipEvent_t* ev = nullptr;
@@ -344,6 +354,23 @@ int kvfold_step_ex(kvfold_cache_t* c, int layer, const void* q, const void* k_ne
   }
   c->len[(size_t)layer] = len_prev + n_tokens;
   return KVFOLD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kvfold_step_ex(kvfold_cache_t* c, int layer, const void* q, const void* k_new, const void* v_new,
+                   int32_t n_tokens, int64_t pos_offset, void* out, float* lse, void* stream) {
+  return step_impl(c, layer, q, k_new, v_new, n_tokens, pos_offset, nullptr, nullptr, out, lse, stream);
+}
+
+int kvfold_step_rope(kvfold_cache_t* c, int layer, const void* q, const void* k_new, const void* v_new,
+                     int32_t n_tokens, int64_t pos_offset, const float* rope_cos, const float* rope_sin, void* out,
+                     float* lse, void* stream) {
+  if (!rope_cos || !rope_sin) return KVFOLD_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(rope_cos) | reinterpret_cast<uintptr_t>(rope_sin)) & 15) return KVFOLD_ERR_INVALID_ARG;
+  return step_impl(c, layer, q, k_new, v_new, n_tokens, pos_offset, rope_cos, rope_sin, out, lse, stream);
 }
 
 int kvfold_step(kvfold_cache_t* c, int layer, const void* q, const void* k_new, const void* v_new, int64_t pos_offset,

@@ -22,6 +22,11 @@ struct AppendParams {
   int32_t row_bytes;  // d * elem_size, multiple of 16
   int64_t capacity;   // rows per head
   int64_t len_prev;   // first destination row
+  // Rotary embedding of the K rows on their way into the cache (nullptr: plain bit copy): angles of the
+  // rows' absolute positions, [C][d/2] fp32 each; V is never rotated.
+  const float* rope_cos;
+  const float* rope_sin;
+  int32_t elem_is_bf16;
 };
 
 struct AttnParams {
@@ -46,6 +51,10 @@ struct AttnParams {
   int32_t pair_order;      // 1: every workgroup is resident at once, two per CU; order them heaviest-first for the
                            // first half and lightest-first for the second so each CU gets a balanced pair
   float scale_log2e;       // softmax scale * log2(e)
+  // Rotary embedding of the queries as they are loaded (nullptr: q is used as handed in): angles of the
+  // chunk's absolute positions, [C][d/2] fp32 each
+  const float* rope_cos;
+  const float* rope_sin;
 };
 
 struct CombineParams {

@@ -105,6 +105,8 @@ def test_null_handles(lib):
     assert kv.kvfold_cache_length(None, 0) == -1
     assert kv.kvfold_step(None, 0, 1, 1, 1, 0, 1, 0) == -1
     assert kv.kvfold_step_ex(None, 0, 1, 1, 1, 1, 0, 1, None, 0) == -1
+    assert kv.kvfold_step_rope(None, 0, 1, 1, 1, 1, 0, 16, 16, 1, None, 0) == -1
+    assert kv.kvfold_step_rope(None, 0, 1, 1, 1, 1, 0, None, None, 1, None, 0) == -1
     assert kv.kvfold_cache_set_length(None, 0, 0) == -1
     assert kv.kvfold_cache_truncate(None, 0, 0) == -1
     assert kv.kvfold_cache_set_tuning(None, 0, 0) == -1

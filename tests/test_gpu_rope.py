@@ -1,0 +1,110 @@
+"""The step that rotates q and k_new itself (rotary embedding at the new tokens' absolute positions, Sec. 2)
+against the oracle's rotation + fold step, and against the plain step fed with inputs rotated beforehand."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_12471_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import fold_harness
+    return fold_harness
+
+
+def _rotated(oracle, x, cos, sin, dtype):
+    """Oracle rotation of a torch tensor [n][heads][d]; returns (stored bits as numpy, torch tensor of the mode dtype)."""
+    r = oracle.rope(x.float().numpy(), cos.numpy(), sin.numpy())
+    if dtype == "bf16":
+        b = oracle.f32_to_bf16_bits(r)
+        return b, torch.from_numpy(b.view(np.int16)).view(torch.bfloat16)
+    return r, torch.from_numpy(r)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("Hq,Hkv,d,chunks,splits,upw", [
+    (8, 2, 128, [160, 160, 50, 96], 0, 0),
+    (8, 2, 128, [64] * 6, 3, 2),
+    (28, 4, 128, [100, 1, 33], 0, 1),
+    (4, 1, 64, [128, 7, 64], 0, 0),
+])
+def test_rope_step_vs_oracle_and_vs_prerotated_inputs(H, oracle, dtype, Hq, Hkv, d, chunks, splits, upw):
+    cfg = I.FoldConfig("rope", 16, 1, Hq, Hkv, d, max(chunks), 0, dtype)
+    cap = sum(chunks)
+    fused = H.GpuFold(cfg, capacity=cap, chunk_tokens=max(chunks))
+    plain = H.GpuFold(cfg, capacity=cap, chunk_tokens=max(chunks))
+    oc = H.make_oracle(oracle, cfg, capacity=cap)
+    for g in (fused, plain):
+        if splits:
+            g.cache.set_tuning(0, splits)
+        if upw and dtype == "bf16":
+            g.cache.set_tuning(1, upw)
+    pos = 0
+    try:
+        for step, C in enumerate(chunks):
+            q, k, v = I.chunk_qkv(cfg, 0, step, n_tokens=C, token_base=pos)
+            cos, sin = I.rope_tables(d, pos, C)
+            out_f, lse_f = fused.step(0, q, k, v, want_lse=True, rope=(cos, sin))
+            # oracle: rotate, store in the mode dtype, then the ordinary fold step
+            q_bits, q_rot = _rotated(oracle, q, cos, sin, dtype)
+            k_bits, k_rot = _rotated(oracle, k, cos, sin, dtype)
+            ref, ref_lse = oc.step(H.wide(q_rot), k_bits, H.bits(v), oc.len)
+            err = np.abs(H.wide(out_f) - ref).max()
+            assert err <= H.TOL[dtype], f"step {step} C={C}: max|out-oracle| = {err}"
+            assert np.abs(lse_f.cpu().double().numpy().T - ref_lse).max() <= (1e-5 if dtype == "f32" else 2e-2)
+            # the plain entry point on inputs rotated beforehand: the same bits
+            out_p, lse_p = plain.step(0, q_rot, k_rot, v, want_lse=True)
+            torch.cuda.synchronize()
+            assert torch.equal(out_f.cpu(), out_p.cpu()), f"step {step}: fused and pre-rotated outputs differ"
+            assert torch.equal(lse_f.cpu(), lse_p.cpu())
+            pos += C
+        H.assert_cache_bit_exact(fused, oc)     # the cache holds the rotated keys, bit for bit the oracle's
+        H.assert_cache_bit_exact(plain, oc)
+    finally:
+        fused.close()
+        plain.close()
+
+
+def test_rope_positions_continue_across_chunks(H, oracle):
+    """Rotating chunk t at positions tC + i (not at i) is what makes the fold equal to one long rotated
+    sequence: outputs of a 4-chunk fold equal those of a single 256-token step with positions 0..255."""
+    cfg = I.FoldConfig("rope_cont", 17, 1, 8, 2, 128, 256, 0, "f32")
+    q, k, v = I.chunk_qkv(cfg, 0, 0, n_tokens=256, token_base=0)
+    cos, sin = I.rope_tables(128, 0, 256)
+    one = H.GpuFold(cfg, capacity=256, chunk_tokens=256)
+    four = H.GpuFold(cfg, capacity=256, chunk_tokens=64)
+    try:
+        whole = one.step(0, q, k, v, rope=(cos, sin)).cpu()
+        parts = [four.step(0, q[s:s + 64], k[s:s + 64], v[s:s + 64], rope=(cos[s:s + 64], sin[s:s + 64])).cpu()
+                 for s in range(0, 256, 64)]
+        assert (torch.cat(parts) - whole).abs().max() <= 2e-6
+        k1, _ = one.cache.view(0)
+        k4, _ = four.cache.view(0)
+        assert torch.equal(k1.cpu(), k4.cpu())
+    finally:
+        one.close()
+        four.close()
+
+
+def test_rope_argument_errors(H):
+    import paper_2605_12471_amd as kv
+    cfg = I.FoldConfig("rope_err", 18, 1, 8, 2, 128, 64, 0, "bf16")
+    g = H.GpuFold(cfg, capacity=128)
+    try:
+        q, k, v = (t.to("cuda:0") for t in I.chunk_qkv(cfg, 0, 0))
+        out = torch.empty_like(q)
+        cos, sin = (t.to("cuda:0") for t in I.rope_tables(128, 0, 64))
+        h = g.cache.handle
+        args = (q.data_ptr(), k.data_ptr(), v.data_ptr())
+        assert kv.kvfold_step_rope(h, 0, *args, 64, 0, None, sin.data_ptr(), out.data_ptr(), None, 0) == -1
+        assert kv.kvfold_step_rope(h, 0, *args, 64, 0, cos.data_ptr(), None, out.data_ptr(), None, 0) == -1
+        assert kv.kvfold_step_rope(h, 0, *args, 64, 0, cos.data_ptr() + 4, sin.data_ptr(), out.data_ptr(), None, 0) == -1
+        assert kv.kvfold_step_rope(h, 0, *args, 64, 5, cos.data_ptr(), sin.data_ptr(), out.data_ptr(), None, 0) == -3
+        assert kv.kvfold_cache_length(h, 0) == 0
+        assert kv.kvfold_step_rope(h, 0, *args, 64, 0, cos.data_ptr(), sin.data_ptr(), out.data_ptr(), None, 0) == 0
+        assert kv.kvfold_cache_length(h, 0) == 64
+    finally:
+        g.close()
