@@ -52,7 +52,7 @@ def step_bytes(cfg, C, L_prev):
 class Workload:
     """All chunks of one layer resident on the GPU + a library cache."""
 
-    def __init__(self, cfg, torch, kv, I, device, n_steps=None, tuning=None):
+    def __init__(self, cfg, torch, kv, I, device, n_steps=None, tuning=None, rope=False):
         self.cfg, self.torch = cfg, torch
         self.n_steps = n_steps or cfg.n_steps
         self.cache = kv.KvFoldCache(1, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.chunk,
@@ -61,13 +61,16 @@ class Workload:
             self.cache.set_tuning(knob, val)
         self.chunks = [I.chunk_qkv(cfg, 0, s, device=device) for s in range(self.n_steps)]
         self.out = torch.empty_like(self.chunks[0][0])
+        # rope: the step rotates q and k_new itself at the chunk's absolute positions (kvfold_step_rope)
+        self.rope = [I.rope_tables(cfg.head_dim, s * cfg.chunk, cfg.chunk, device=device) for s in range(self.n_steps)] \
+            if rope else [None] * self.n_steps
         self.flops = sum(step_flops(cfg, cfg.chunk, s * cfg.chunk) for s in range(self.n_steps))
         self.bytes = sum(step_bytes(cfg, cfg.chunk, s * cfg.chunk) for s in range(self.n_steps))
 
     def fold(self):
         self.cache.set_length(0, 0)
         for s, (q, k, v) in enumerate(self.chunks):
-            self.cache.step(0, q, k, v, self.out, pos_offset=s * self.cfg.chunk)
+            self.cache.step(0, q, k, v, self.out, pos_offset=s * self.cfg.chunk, rope=self.rope[s])
 
     def per_step_curve(self, reps=3):
         """Event-timed single steps against a cache rewound to each length: [(L_prev, ms)]."""
@@ -296,6 +299,13 @@ def main():
             }
             w2.close()
         extra["decode_shaped_128k"] = decode_shaped_points(torch, kv, I, dev)
+        # the headline fold with unrotated inputs: rotary embedding applied inside the step
+        w3 = Workload(cfg, torch, kv, I, dev, tuning=tuning, rope=True)
+        ms3 = time_folds(w3, torch, args.steps, args.warmup)
+        extra["fold_" + cfg.name + "_rope_in_step"] = {
+            "ms_per_fold": ms3, "tflops": w3.flops / (ms3 * 1e-3) / 1e12, "ms_per_fold_without": ms,
+            "note": "same workload through kvfold_step_rope (q, k_new unrotated; cos/sin tables resident)"}
+        w3.close()
     result["extra"] = extra
     print(json.dumps(result))
 
