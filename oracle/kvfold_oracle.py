@@ -106,6 +106,25 @@ def rope(x: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
     return out
 
 
+def storage_roundtrip(bits16: np.ndarray, n_bits: int) -> np.ndarray:
+    """The paper's storage perturbation (Sec. 8, Discussion: a per-step quantisation round trip
+    bf16 -> intN -> bf16 of the carried cache), applied to rows as they join the cache.  The paper gives
+    no quantiser; the reading taken: one group = the d elements of one (token, KV head) row, symmetric,
+    scale = max|x| / (2^(N-1) - 1), code = round-half-even(x / scale) clamped to +-(2^(N-1) - 1),
+    value = code * scale, all in fp32, stored as bf16 (RNE).  An all-zero row stays zero.
+    bits16: [..., d] bf16 bit patterns; returns the same shape."""
+    assert n_bits in (4, 8)
+    x = bf16_bits_to_f32(bits16)
+    qmax = np.float32(2 ** (n_bits - 1) - 1)
+    amax = np.abs(x).max(axis=-1, keepdims=True).astype(np.float32)
+    scale = (amax / qmax).astype(np.float32)
+    safe = np.where(scale > 0, scale, np.float32(1.0)).astype(np.float32)
+    code = np.clip(np.rint((x / safe).astype(np.float32)), -qmax, qmax).astype(np.float32)
+    y = (code * safe).astype(np.float32)
+    y = np.where(scale > 0, y, np.float32(0.0)).astype(np.float32)
+    return f32_to_bf16_bits(y).reshape(bits16.shape)
+
+
 class OracleCache:
     """Carried KV cache of ONE layer plus the fold step on it.
 

@@ -356,3 +356,37 @@ def test_rope_tables_generator_matches_its_formula():
     cos, sin = I.rope_tables(8, 100, 3, theta=10000.0)
     ang = np.arange(100, 103)[:, None] * 10000.0 ** (-2.0 * np.arange(4) / 8)[None, :]
     assert np.allclose(cos.numpy(), np.cos(ang), atol=1e-7) and np.allclose(sin.numpy(), np.sin(ang), atol=1e-7)
+
+
+# ---- storage round trip bf16 -> intN -> bf16 of rows joining the cache (Sec. 8, Discussion)
+
+@pytest.mark.parametrize("n_bits", [8, 4])
+def test_storage_roundtrip_properties(oracle, n_bits):
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((200, 3, 128)).astype(np.float32) * rng.uniform(0.01, 30.0, (200, 3, 1)).astype(np.float32)
+    x[7] = 0.0
+    b = oracle.f32_to_bf16_bits(x)
+    xb = oracle.bf16_bits_to_f32(b).astype(np.float64)
+    y = oracle.bf16_bits_to_f32(oracle.storage_roundtrip(b, n_bits)).astype(np.float64)
+    qmax = 2 ** (n_bits - 1) - 1
+    amax = np.abs(xb).max(-1, keepdims=True)
+    step = amax / qmax
+    assert np.all(y[7] == 0.0)                                                    # zero row stays zero
+    assert np.all(np.abs(y - xb) <= step / 2 * 1.0001 + np.abs(y) * 2.0 ** -8)      # half a step + bf16 rounding
+    for r in (0, 50, 199):                                                        # at most 2^N - 1 levels per group
+        assert len(np.unique(y[r, 1])) <= 2 * qmax + 1
+    assert np.allclose(np.abs(y).max(-1), amax[..., 0], rtol=2.0 ** -7)           # the largest element survives
+    sign_ok = (np.sign(y) == np.sign(xb)) | (y == 0)
+    assert sign_ok.all()
+    rel = np.sqrt(((y - xb) ** 2).sum() / (xb ** 2).sum())
+    assert (rel < 0.012) if n_bits == 8 else (0.03 < rel < 0.2)                   # N(0,1) rows: ~0.7 % / ~11 %
+
+
+def test_storage_roundtrip_small_case_by_hand(oracle):
+    """d = 4, int4 (codes -7..7): row (7, -3.5, 1, 0.49) has scale 1: codes 7, -4 (tie to even), 1, 0."""
+    x = np.array([[7.0, -3.5, 1.0, 0.49]], np.float32)
+    y = oracle.bf16_bits_to_f32(oracle.storage_roundtrip(oracle.f32_to_bf16_bits(x), 4))
+    assert np.array_equal(y, np.array([[7.0, -4.0, 1.0, 0.0]], np.float32))
+    x = np.array([[127.0, 63.5, -0.5, 2.4]], np.float32)                          # int8, scale 1: 127, 64, -0, 2
+    y = oracle.bf16_bits_to_f32(oracle.storage_roundtrip(oracle.f32_to_bf16_bits(x), 8))
+    assert np.array_equal(y, np.array([[127.0, 64.0, -0.0, 2.0]], np.float32))
