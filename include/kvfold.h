@@ -180,6 +180,20 @@ int kvfold_cache_truncate(kvfold_cache_t* cache, int layer, int64_t new_len);
 int kvfold_cache_set_length(kvfold_cache_t* cache, int layer, int64_t new_len);
 
 /*
+ * Storage perturbation of the carried cache (Sec. 8, Discussion: a per-step
+ * quantisation round trip bf16 -> intN -> bf16).  n_bits = 8 or 4: from now on
+ * every step passes the K and V rows it appends through that integer width and
+ * back, in place, before its queries attend to them; 0 switches it off.  The
+ * paper names no quantiser; the one used: a group is the head_dim elements of
+ * one (token, KV head) row, symmetric, scale = max|x| / (2^(N-1) - 1), code =
+ * round-half-even(x / scale) clamped to +-(2^(N-1) - 1), x' = code * scale, in
+ * fp32, stored as bf16 (RNE); an all-zero row stays zero.  bf16 caches only
+ * (KVFOLD_ERR_UNSUPPORTED otherwise); other values KVFOLD_ERR_INVALID_ARG.
+ * Host-only; applies to steps enqueued after the call.
+ */
+int kvfold_cache_set_storage_roundtrip(kvfold_cache_t* cache, int32_t n_bits);
+
+/*
  * Tuning knobs for measurements (defaults are chosen automatically per step).
  *   KVFOLD_TUNE_SPLITS         number of prefix splits of the attention kernel; 0 = automatic.
  *                              Clamped to what the split workspace and the key range allow.

@@ -80,6 +80,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvfold_cache_truncate.restype = ctypes.c_int
     lib.kvfold_cache_set_length.argtypes = [vp, ctypes.c_int, i64]
     lib.kvfold_cache_set_length.restype = ctypes.c_int
+    lib.kvfold_cache_set_storage_roundtrip.argtypes = [vp, i32]
+    lib.kvfold_cache_set_storage_roundtrip.restype = ctypes.c_int
     lib.kvfold_cache_set_tuning.argtypes = [vp, i32, i32]
     lib.kvfold_cache_set_tuning.restype = ctypes.c_int
     lib.kvfold_cache_plan.argtypes = [vp, i32, i64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
@@ -155,6 +157,10 @@ def kvfold_cache_truncate(cache, layer, new_len) -> int:
 
 def kvfold_cache_set_length(cache, layer, new_len) -> int:
     return load_library().kvfold_cache_set_length(cache, layer, new_len)
+
+
+def kvfold_cache_set_storage_roundtrip(cache, n_bits) -> int:
+    return load_library().kvfold_cache_set_storage_roundtrip(cache, n_bits)
 
 
 def kvfold_cache_set_tuning(cache, knob, value) -> int:
@@ -268,6 +274,11 @@ class KvFoldCache:
         rc = kvfold_cache_set_length(self.handle, layer, new_len)
         if rc:
             raise KvFoldError(rc, "kvfold_cache_set_length")
+
+    def set_storage_roundtrip(self, n_bits):
+        rc = kvfold_cache_set_storage_roundtrip(self.handle, n_bits)
+        if rc:
+            raise KvFoldError(rc, "kvfold_cache_set_storage_roundtrip")
 
     def set_tuning(self, knob, value):
         rc = kvfold_cache_set_tuning(self.handle, knob, value)

@@ -67,6 +67,60 @@ __global__ void __launch_bounds__(256) append_rope_kernel(AppendParams p) {
   }
 }
 
+// Storage perturbation of the carried cache (Sec. 8, Discussion: a per-step quantisation round trip
+// bf16 -> intN -> bf16), applied in place to the rows a step has just appended (K and V).  The paper
+// names no quantiser; the reading: one group = the d elements of one (token, KV head) row, symmetric,
+//   scale = max|x| / (2^(N-1) - 1),  code = round-half-even(x / scale) clamped to +-(2^(N-1) - 1),
+//   x' = code * scale,
+// all in fp32, stored as bf16 (RNE); an all-zero row stays zero.  A lane owns 16 bytes (8 elements), the
+// d / 8 lanes of a row agree on the maximum by butterfly exchanges inside their lane group.
+__global__ void __launch_bounds__(256) storage_roundtrip_kernel(AppendParams p, float qmax) {
+  typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+  const bool is_v = blockIdx.y != 0;
+  bf16x8* __restrict__ cache = reinterpret_cast<bf16x8*>(is_v ? p.v_cache : p.k_cache);
+  const int vec_per_row = p.row_bytes >> 4;  // 8 or 16 lanes per row: a power of two, rows never straddle a wavefront
+  const int64_t per_head = (int64_t)p.n_tokens * vec_per_row;
+  const int64_t total = per_head * p.n_kv_heads;
+  const int64_t padded = (total + 255) / 256 * 256;  // whole lane groups stay together through the exchanges
+  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < padded; idx += (int64_t)gridDim.x * blockDim.x) {
+    const bool live = idx < total;
+    const int64_t cidx = live ? idx : total - 1;
+    const int64_t g = cidx / per_head;
+    const int64_t rem = cidx - g * per_head;
+    const int64_t i = rem / vec_per_row;
+    const int64_t c = rem - i * vec_per_row;
+    bf16x8* at = cache + (g * p.capacity + p.len_prev + i) * vec_per_row + c;
+    bf16x8 v = *at;
+    float x[8], amax = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      x[e] = (float)v[e];
+      amax = fmaxf(amax, fabsf(x[e]));
+    }
+    for (int off = 1; off < vec_per_row; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    const float scale = amax / qmax;
+    if (live && scale > 0.f) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float code = rintf(x[e] / scale);
+        code = fminf(fmaxf(code, -qmax), qmax);
+        v[e] = (__bf16)(code * scale);
+      }
+      *at = v;
+    }
+  }
+}
+
+hipError_t launch_storage_roundtrip(const AppendParams& p, int n_bits, hipStream_t s) {
+  const int64_t total = (int64_t)p.n_tokens * p.n_kv_heads * (p.row_bytes >> 4);
+  if (total <= 0) return hipSuccess;
+  int64_t blocks = (total + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(storage_roundtrip_kernel, dim3((unsigned)blocks, 2), dim3(256), 0, s, p,
+                     (float)((1 << (n_bits - 1)) - 1));
+  return hipGetLastError();
+}
+
 hipError_t launch_append(const AppendParams& p, hipStream_t s) {
   const int64_t total = (int64_t)p.n_tokens * p.n_kv_heads * (p.row_bytes >> 4);
   if (total <= 0) return hipSuccess;

@@ -31,6 +31,7 @@ struct kvfold_cache {
   std::vector<int64_t> len;
   int tune_splits;
   int tune_units_per_wave;
+  int storage_bits;  // 0, or 4 / 8: rows are round-tripped through that integer width as they join the cache
   // optional per-kernel timing: 4 events per step (before append, after append, after attention, after merge)
   std::vector<hipEvent_t> prof_events;
   std::vector<char> prof_has_merge;
@@ -207,6 +208,7 @@ int kvfold_cache_create(const kvfold_config_t* cfg, kvfold_cache_t** out_cache) 
   c->ws_rows = 0;
   c->tune_splits = 0;
   c->tune_units_per_wave = 0;
+  c->storage_bits = 0;
   c->len.assign((size_t)cfg->n_layers, 0);
 
   hipDeviceProp_t prop;
@@ -328,6 +330,10 @@ int step_impl(kvfold_cache_t* c, int layer, const void* q, const void* k_new, co
   }
   e = launch_append(ap, s);
   if (e != hipSuccess) return hip_fail(e);
+  if (c->storage_bits) {
+    e = launch_storage_roundtrip(ap, c->storage_bits, s);
+    if (e != hipSuccess) return hip_fail(e);
+  }
   if (ev) (void)hipEventRecord(ev[1], s);
   e = (f.dtype == KVFOLD_BF16) ? launch_attn_bf16(at, f.head_dim, pl.units_per_wave, s) : launch_attn_f32(at, f.head_dim, s);
   if (e != hipSuccess) return hip_fail(e);
@@ -440,6 +446,14 @@ int kvfold_cache_set_length(kvfold_cache_t* c, int layer, int64_t new_len) {
     for (auto& v : c->len) v = new_len;
   else
     c->len[(size_t)layer] = new_len;
+  return KVFOLD_OK;
+}
+
+int kvfold_cache_set_storage_roundtrip(kvfold_cache_t* c, int32_t n_bits) {
+  if (!c) return KVFOLD_ERR_INVALID_ARG;
+  if (n_bits != 0 && n_bits != 4 && n_bits != 8) return KVFOLD_ERR_INVALID_ARG;
+  if (n_bits != 0 && c->cfg.dtype != KVFOLD_BF16) return KVFOLD_ERR_UNSUPPORTED;
+  c->storage_bits = n_bits;
   return KVFOLD_OK;
 }
 

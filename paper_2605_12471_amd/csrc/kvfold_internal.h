@@ -71,6 +71,8 @@ struct CombineParams {
 };
 
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
+// In-place storage round trip bf16 -> intN -> bf16 (n_bits = 4 or 8) of cache rows [len_prev, len_prev + C) of K and V.
+hipError_t launch_storage_roundtrip(const AppendParams& p, int n_bits, hipStream_t s);
 hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, int units_per_wave, hipStream_t s);
 hipError_t launch_attn_f32(const AttnParams& p, int head_dim, hipStream_t s);
 hipError_t launch_combine(const CombineParams& p, hipStream_t s);

@@ -110,6 +110,7 @@ def test_null_handles(lib):
     assert kv.kvfold_cache_set_length(None, 0, 0) == -1
     assert kv.kvfold_cache_truncate(None, 0, 0) == -1
     assert kv.kvfold_cache_set_tuning(None, 0, 0) == -1
+    assert kv.kvfold_cache_set_storage_roundtrip(None, 8) == -1
     assert kv.kvfold_cache_plan(None, 1, 1)[0] == -1
     assert kv.kvfold_cache_view(None, 0)[0] == -1
     assert kv.kvfold_cache_profile_begin(None, 1) == -1
