@@ -197,6 +197,37 @@ def decode_shaped_points(torch, kv, I, dev, L=131072, chunks=(1, 4, 16), reps=20
     return pts
 
 
+def fp32_last_step(torch, kv, I, dev, reps=3):
+    """The fp32 correctness mode on the last step of the sweep workload at C=2048 (Hq=28, Hkv=4, d=128, 62K-key
+    prefix), against the fp32 MFMA peak.  The prefix rows are seeded N(0,1) written in place."""
+    cfg = I.CONFIGS["sweep_64k"]
+    C, L = 2048, cfg.total_tokens
+    Lp = L - C
+    cache = kv.KvFoldCache(1, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, C, L, "f32", device=dev.index or 0)
+    g = torch.Generator(device=dev)
+    g.manual_seed(I.BASE_SEED + 77)
+    K, V = cache.view(0)
+    K.normal_(generator=g)
+    V.normal_(generator=g)
+    q, k, v = (torch.randn((C, h, cfg.head_dim), device=dev, generator=g)
+               for h in (cfg.n_q_heads, cfg.n_kv_heads, cfg.n_kv_heads))
+    out = torch.empty_like(q)
+    best = None
+    for _ in range(reps):
+        cache.set_length(0, Lp)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        cache.step(0, q, k, v, out, pos_offset=Lp)
+        e1.record()
+        e1.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None else min(best, ms)
+    cache.close()
+    fl = step_flops(cfg.with_(dtype="f32"), C, Lp)
+    return {"C": C, "L_prev": Lp, "ms": best, "tflops": fl / (best * 1e-3) / 1e12,
+            "frac_of_fp32_mfma_peak": fl / (best * 1e-3) / 1e12 / PEAK_FP32_TFLOPS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -299,6 +330,7 @@ def main():
             }
             w2.close()
         extra["decode_shaped_128k"] = decode_shaped_points(torch, kv, I, dev)
+        extra["fp32_mode_sweep_64k_last_step"] = fp32_last_step(torch, kv, I, dev)
         # the headline fold with unrotated inputs: rotary embedding applied inside the step
         w3 = Workload(cfg, torch, kv, I, dev, tuning=tuning, rope=True)
         ms3 = time_folds(w3, torch, args.steps, args.warmup)
