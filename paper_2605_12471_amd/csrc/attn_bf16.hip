@@ -104,9 +104,10 @@ __device__ __forceinline__ void mfma_settle_a(floatx16& x) {
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(x));
 }
 
-#ifndef KVFOLD_NV2
-#define KVFOLD_NV2 3  // V ring slots of the two-units-per-wave kernel (K ring has one more)
-#endif
+// V ring slots (the K ring has one more): three for the two-unit kernel, one workgroup per CU, 112 KB of
+// LDS; two for the one-unit kernel so that two workgroups share a CU's 160 KB.  A deeper ring bought
+// nothing in measurements, neither on L2-resident prefixes nor on HBM-bound decode-shaped steps.
+constexpr int kRingTwoUnits = 3, kRingOneUnit = 2;
 constexpr float kRescaleThreshold = 16.0f;  // log2 units: stale running max tolerated up to 2^16
 constexpr float kSumThreshold = 1048576.0f;             // 2^20: row sum of a half that moves the reference up
 constexpr float kRedoThreshold = 1152921504606846976.0f;  // 2^60: beyond this the workgroup starts over
@@ -791,7 +792,12 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
 template <int D, int QB, int NV>
 static hipError_t launch_one(const AttnParams& p, hipStream_t s) {
   constexpr int lds_bytes = (2 * NV + 1) * kTileKeys * D * 2;
-  static bool attr_set = false;  // idempotent; a benign race at worst sets it twice
+  // per device: the attribute belongs to the device's copy of the kernel (idempotent; a benign race at worst
+  // sets it twice)
+  static bool attr_done[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  bool& attr_set = attr_done[dev];
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, QB, NV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
@@ -803,8 +809,8 @@ static hipError_t launch_one(const AttnParams& p, hipStream_t s) {
 }
 
 hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, int qb, hipStream_t s) {
-  if (head_dim == 128) return qb == 2 ? launch_one<128, 2, KVFOLD_NV2>(p, s) : launch_one<128, 1, 2>(p, s);
-  if (head_dim == 64) return qb == 2 ? launch_one<64, 2, 3>(p, s) : launch_one<64, 1, 2>(p, s);
+  if (head_dim == 128) return qb == 2 ? launch_one<128, 2, kRingTwoUnits>(p, s) : launch_one<128, 1, kRingOneUnit>(p, s);
+  if (head_dim == 64) return qb == 2 ? launch_one<64, 2, kRingTwoUnits>(p, s) : launch_one<64, 1, kRingOneUnit>(p, s);
   return hipErrorInvalidValue;
 }
 
