@@ -9,9 +9,8 @@
 //  * Work unit = (32 consecutive chunk rows, one query head).  A wavefront owns QB units, a
 //    workgroup 4 wavefronts; all units of a workgroup share one KV head, so a K/V tile staged in
 //    LDS is reused across the grouped-query heads, and with QB = 2 every K/V fragment read from
-//    LDS feeds two MFMAs (LDS bandwidth, not the matrix pipe, is the limit at QB = 1).  Units are
-//    ordered token-block-major, head-minor, so the wavefronts of a workgroup see (almost) the same
-//    key range and only the last tiles need the causal mask.
+//    LDS feeds two MFMAs.  Units are ordered token-block-major, head-minor, so the wavefronts of a
+//    workgroup see (almost) the same key range and only the last tiles need the causal mask.
 //  * 64-key K/V tiles travel HBM/L2 -> LDS with global_load_lds_dwordx4 (no registers), several
 //    tiles ahead, into rings of NV+1 (K) and NV (V) slots; the XOR swizzle that makes the later
 //    LDS reads conflict-free is applied by choosing which 16-byte chunk each lane fetches.
@@ -22,8 +21,10 @@
 //    O^T = V^T P^T; V^T fragments are read from the row-major V tile with the LDS transpose read
 //    (ds_read_b64_tr_b16) using the same permutation, so P never leaves registers.
 //  * Software pipeline inside the wavefront, in half tiles of 32 keys: while the matrix pipe forms
-//    S^T of half h+1 the vector ALU turns S^T of half h into P (exp2, bf16 pack, row sums); the
-//    matrix pipe then accumulates O^T of half h.
+//    S^T of half h+1 and then accumulates O^T of half h, the vector ALU turns S^T of half h into P
+//    (exp2, bf16 pack, row sums) -- one exp2 behind every MFMA, the first quarter of a half already
+//    in the tail of the step before, because a single wavefront hides only about 16-20 cycles of
+//    other instructions under each 32-cycle MFMA.
 //  * Online softmax in base 2 with ONE vector instruction per logit: the queries are multiplied by
 //    scale*log2(e) once (and rounded to bf16 again), and the S^T accumulators start from -m (the
 //    running row max) instead of 0, so the matrix pipe delivers S*scale*log2e - m and P is a bare
@@ -45,7 +46,6 @@ namespace kvfold {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short short4_;
 typedef __attribute__((ext_vector_type(8))) short short8_;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
@@ -311,13 +311,6 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=a"(f) : "v"(kaddr[ks]), "n"(HALFB));
     return f;
   };
-  auto v_frag = [&](int tt, int db, int imm) __attribute__((always_inline)) -> bf16x8 {
-    const unsigned a0 = vaddr[db] + (unsigned)(imm + 16 * tt * ROWB);
-    const short4_ lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0));
-    const short4_ hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4_, a0 + (unsigned)(8 * ROWB)));
-    const short8_ a8 = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, a8);
-  };
   // causal mask of the 32-key half hh
   auto mask_half = [&](floatx16 (&s)[QB], int hh) __attribute__((always_inline)) {
     // (opaque copies: whatever is derived from them is computed here, not once ahead of all loops and
@@ -455,7 +448,8 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   static_assert(SUM_MODE || RM0 >= M1 + 1, "row maxima would read S^T before its MFMAs retire");
   static_assert(SUM_MODE || (RM1 > RM0 && RM1 + QB < M), "no room for the row maxima");
   static_assert(LPG <= (M - EW) * 4, "ring refill does not fit the tail");
-  // read r is issued in slot r * RW / R, event j in slot j * EW / NE; reads issued before slot sl:
+  // read r is issued in slot r * RW / R; main event j >= NEAR in slot (j - NEAR) * EW / NMAIN, early event j < NEAR
+  // of the next half in slot EW + j * (M - EW) / NEAR; reads issued before slot sl:
   auto rd_before = [](int sl) constexpr { int n = 0; for (int r = 0; r < R; ++r) n += (r * RW / R) < sl; return n; };
 
   floatx16 sA[QB], sB[QB];
