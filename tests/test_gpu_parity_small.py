@@ -130,3 +130,35 @@ def test_layers_are_independent(H, oracle):
             H.assert_cache_bit_exact(gpu, ocs[layer], layer)
     finally:
         gpu.close()
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        d = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 3, 4]))
+        G = int(rng.choice([1, 2, 4, 7]))
+        n_chunks = int(rng.integers(1, 5))
+        chunks = [int(rng.choice([1, 5, 31, 32, 33, 64, 100, 128, 200, 256])) for _ in range(n_chunks)]
+        dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+        splits = int(rng.choice([0, 0, 2, 4]))
+        upw = int(rng.choice([0, 0, 1, 2]))
+        cases.append((dtype, Hkv * G, Hkv, d, tuple(chunks), splits, upw))
+    return cases
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,chunks,splits,upw", _random_cases(28, 20260512))
+def test_seeded_random_shapes(H, oracle, dtype, Hq, Hkv, d, chunks, splits, upw):
+    """A seeded sweep over head counts, group sizes, head dims, ragged chunk sequences and launch shapes: every
+    row and head of every step against the oracle, cache bit-exact."""
+    cfg = I.FoldConfig("rand", 21, 1, Hq, Hkv, d, max(chunks), 0, dtype)
+    _run_case(H, oracle, cfg, list(chunks), splits=splits, upw=upw if dtype == "bf16" else 0)
+
+
+@pytest.mark.parametrize("d,upw", [(64, 2), (64, 1), (128, 2)])
+def test_long_prefix_small_case(H, oracle, d, upw):
+    """4K tokens in chunks of 512: enough tiles for the unmasked main loop, the ring to wrap many times and the
+    clamp-free refill path, on both head dims and both wave shapes."""
+    cfg = I.FoldConfig("longish", 22, 1, 8, 2, d, 512, 0, "bf16")
+    _run_case(H, oracle, cfg, [512] * 8, upw=upw)
