@@ -112,6 +112,53 @@ constexpr float kRescaleThreshold = 16.0f;  // log2 units: stale running max tol
 constexpr float kSumThreshold = 1048576.0f;             // 2^20: row sum of a half that moves the reference up
 constexpr float kRedoThreshold = 1152921504606846976.0f;  // 2^60: beyond this the workgroup starts over
 
+// Slot schedule of one pipeline step of a wavefront with QA active units (QA = QB in the ordinary
+// step; QA = 1 in a two-unit wavefront whose first unit has passed its causal horizon).  A step
+// handles one 32-key half hh and consists of M MFMA slots: M1 slots forming S^T of half hh+1 (phase
+// 1), then M2 slots accumulating O^T += V^T P^T of half hh (phase 2).  A single wavefront hides only
+// about 16-20 cycles of other instructions under one 32-cycle MFMA (an exp2 costs 8, plain vector
+// instructions 4), so everything else is dealt out evenly, a fixed share behind every MFMA:
+//   * exp2 / pack / row-sum "events" of half hh (one event = one exp2; the second event of a logit
+//     pair also packs the pair, and each event adds the exp2 before it to the row sum): events
+//     [NEAR, NE) in slots [0, EW) of the half's own step, so that slab 0 of P is packed before phase
+//     2 and slab 1 before its second half; with SUM_MODE the first NEAR events (all in slab 0) are
+//     taken EARLY, in the tail slots [EW, M) of the step before, as soon as that S^T is complete;
+//   * LDS fragment reads one batch ahead, in slots [0, RW), one wait per batch;
+//   * SUM_MODE: the test of the row sums against 2^20 right after the last event; else the row
+//     maxima of half hh+1 and the rescale decision in the exp-free tail [RM0, M);
+//   * in odd steps the workgroup barrier and the ring refill (DMA) in the tail [EW, M).
+template <int D, int QA, bool SUM_MODE, int LPG>
+struct Sched {
+  static constexpr int KS = D / 16, DB = D / 32;
+  static constexpr int M1 = KS * QA;       // MFMAs of phase 1 (K fragment ks feeds QA of them)
+  static constexpr int M2 = 2 * DB * QA;   // MFMAs of phase 2 (V^T fragment (tt, db) feeds QA of them)
+  static constexpr int M = M1 + M2;
+  static constexpr int NP = QA * 8;        // logit pairs per step; pair k: slab k / (4 QA), unit (k / 4) % QA
+  static constexpr int NE = 2 * NP;        // exp events
+  static constexpr int EW = M1 + M2 / 2;
+  static constexpr int NEAR = SUM_MODE ? (NE * (M - EW) / M) & ~1 : 0;
+  static constexpr int NMAIN = NE - NEAR;
+  static_assert(NEAR <= NE / 2, "early events must stay inside slab 0");
+  static_assert(NEAR + (M1 * NMAIN + EW - 1) / EW >= NE / 2, "slab 0 would not be complete at the start of phase 2");
+  static constexpr int GK = KS / 2;        // K fragments per batch (two batches per step)
+  static constexpr int GV = DB;            // V^T fragments per batch (two batches per step, 2 reads each)
+  static constexpr int R = 2 * GK + 4 * GV;  // LDS read instructions per step, in issue order:
+                                             //   kg[1] (GK) | vg[0] (2 GV) | vg[1] (2 GV) | kg[0] of the next step (GK)
+  static constexpr int RW = EW;
+  static_assert(EW + 1 < M, "no slot for the row-sum test");
+  static constexpr int RM1 = M - 1 - QA;   // row-max slots [RM0, RM1), then QA + 1 decision slots
+  static constexpr int RM0 = (EW - (M >= 32 ? 2 : 0)) < RM1 ? (EW - (M >= 32 ? 2 : 0)) : RM1 - 1;
+  static_assert(SUM_MODE || RM0 >= M1 + 1, "row maxima would read S^T before its MFMAs retire");
+  static_assert(SUM_MODE || (RM1 > RM0 && RM1 + QA < M), "no room for the row maxima");
+  static_assert(LPG <= (M - EW) * 4, "ring refill does not fit the tail");
+  // read r is issued in slot r * RW / R; reads issued before slot sl:
+  static constexpr int rd_before(int sl) {
+    int n = 0;
+    for (int r = 0; r < R; ++r) n += (r * RW / R) < sl;
+    return n;
+  }
+};
+
 template <int D, int QB, int NV>
 __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnParams p) {
   // Sum-driven reference updates (no row max below the causal horizon) for the two-unit kernel, whose
@@ -167,15 +214,26 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   bool store_ok[QB];
   int my_vis[QB];     // keys visible to this lane's query row
   int vis_first[QB];  // keys visible to the unit's first row (key blocks entirely below need no mask)
+  int vis_last0 = 0;  // keys visible to the last row of unit 0: tiles entirely beyond are dead for it
+  // pair_units (two-unit kernel): wavefront number n = 4 ug + w of the KV head owns unit n, counted from
+  // the first token block, and unit U-1-n, counted from the last, so that every wavefront has the
+  // same number of (row, key) pairs to do whatever the causal horizon; else units 2n and 2n+1.
+  const bool pair_units = QB == 2 && p.pair_units;
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    const int u = (ug * kUnitsPerWg + w) * QB + qb;
-    const int uc = u < p.units_per_head ? u : p.units_per_head - 1;
+    const int n = ug * kUnitsPerWg + w;
+    const int u = !pair_units ? n * QB + qb : (qb == 0 ? n : p.units_per_head - 1 - n);
+    const bool valid = !pair_units ? u < p.units_per_head : (qb == 0 ? 2 * n <= p.units_per_head - 1 : 2 * n < p.units_per_head - 1);
+    const int uc = u < 0 ? 0 : (u < p.units_per_head ? u : p.units_per_head - 1);
     const int tb = uc / G, hg = uc - tb * G;
     head[qb] = g * G + hg;
     tok[qb] = tb * kRowsPerUnit + m;
     const int tokc = tok[qb] < C ? tok[qb] : C - 1;
-    store_ok[qb] = (u < p.units_per_head) && (tok[qb] < C);
+    store_ok[qb] = valid && (tok[qb] < C);
+    if (qb == 0) {
+      const int last = tb * kRowsPerUnit + kRowsPerUnit - 1;
+      vis_last0 = (int)p.len_prev + (last < C ? last : C - 1) + 1;
+    }
     my_vis[qb] = (int)p.len_prev + tokc + 1;
     vis_first[qb] = (int)p.len_prev + tb * kRowsPerUnit + 1;
     const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ((int64_t)tokc * Hq + head[qb]) * D;
@@ -207,8 +265,10 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   // ---- tile range of this workgroup / split
   int nkeys_wg;
   {
-    int ulast = ug * UPW + UPW - 1;
+    // the unit of the workgroup with the farthest horizon: its last one, or with pair_units the partner of its first
+    int ulast = pair_units ? p.units_per_head - 1 - ug * kUnitsPerWg : ug * UPW + UPW - 1;
     if (ulast > p.units_per_head - 1) ulast = p.units_per_head - 1;
+    if (ulast < 0) ulast = 0;
     int row_hi = (ulast / G) * kRowsPerUnit + kRowsPerUnit - 1;
     if (row_hi > C - 1) row_hi = C - 1;
     nkeys_wg = (int)p.len_prev + row_hi + 1;
@@ -312,13 +372,14 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     return f;
   };
   // causal mask of the 32-key half hh
-  auto mask_half = [&](floatx16 (&s)[QB], int hh) __attribute__((always_inline)) {
+  auto mask_half = [&](floatx16 (&s)[QB], int hh, int q0 = 0) __attribute__((always_inline)) {
     // (opaque copies: whatever is derived from them is computed here, not once ahead of all loops and
     // then held in registers through the unmasked main loop)
     int hi_here = hi;
     asm volatile("" : "+v"(hi_here));
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
+      if (qb < q0) continue;
       if (hh * 32 + 32 > vis_first[qb]) {  // wave-uniform
         int vis_here = my_vis[qb];
         asm volatile("" : "+v"(vis_here));
@@ -333,22 +394,24 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   // by how much the max would grow.  The running max is raised only when it lags by more than
   // 2^16 (or has never been set).  The decision (cross-lane max, compare) is taken early, under
   // the matrix pipe; the branch comes later.
-  auto rescale_need = [&](const float (&dm)[QB]) __attribute__((always_inline)) -> bool {
+  auto rescale_need = [&](const float (&dm)[QB], int q0 = 0) __attribute__((always_inline)) -> bool {
     int need = 0;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)  // no short-circuit: plain lane-wise compares, one wave-wide reduction at the end
-      need |= (int)(dm[qb] > kRescaleThreshold) | ((int)(m_run[qb] == -INFINITY) & (int)(dm[qb] > -INFINITY));
+      if (qb >= q0) need |= (int)(dm[qb] > kRescaleThreshold) | ((int)(m_run[qb] == -INFINITY) & (int)(dm[qb] > -INFINITY));
     return __any(need);
   };
-  auto rescale_decide = [&](const float (&mx)[QB], float (&dm)[QB]) __attribute__((always_inline)) -> bool {
+  auto rescale_decide = [&](const float (&mx)[QB], float (&dm)[QB], int q0 = 0) __attribute__((always_inline)) -> bool {
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) dm[qb] = pair_max(mx[qb]);
-    return rescale_need(dm);
+    for (int qb = 0; qb < QB; ++qb)
+      if (qb >= q0) dm[qb] = pair_max(mx[qb]);
+    return rescale_need(dm, q0);
   };
   // s holds the logits of the half the maxima came from: they were formed against the old max
-  auto rescale_apply = [&](const float (&dm)[QB], floatx16 (&s)[QB]) __attribute__((always_inline)) {
+  auto rescale_apply = [&](const float (&dm)[QB], floatx16 (&s)[QB], int q0 = 0) __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
+      if (qb < q0) continue;
       const float cur = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
       // only rows that asked for it move, so a row's arithmetic never depends on its wave neighbours
       const bool mine = (dm[qb] > kRescaleThreshold) || (m_run[qb] == -INFINITY && dm[qb] > -INFINITY);
@@ -375,9 +438,10 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   // above 2^20 moves the reference up by the power of two just above it, which is exact; s holds
   // the in-flight logits of the next half, formed against the old reference.  Both lanes of a row
   // decide on the larger of their two sums, so a row never depends on its wave neighbours.
-  auto rescale_from_sum = [&](const float (&ls)[QB], floatx16 (&s)[QB]) __attribute__((always_inline)) {
+  auto rescale_from_sum = [&](const float (&ls)[QB], floatx16 (&s)[QB], int q0 = 0) __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
+      if (qb < q0) continue;
       const float tot = pair_max(ls[qb]);
       const bool bad = !(tot <= kRedoThreshold);  // also infinite or NaN
       overflowed |= __any((int)bad);
@@ -402,9 +466,10 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       }
     }
   };
-  auto rowmax_all = [&](floatx16 (&s)[QB], float (&mx)[QB]) __attribute__((always_inline)) {
+  auto rowmax_all = [&](floatx16 (&s)[QB], float (&mx)[QB], int q0 = 0) __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
+      if (qb < q0) continue;
       float a = fmaxf(s[qb][0], s[qb][1]);
 #pragma unroll
       for (int r = 2; r < 16; r += 2) a = fmaxf(fmaxf(a, s[qb][r]), s[qb][r + 1]);
@@ -412,45 +477,8 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     }
   };
 
-  // ---- the software pipeline -----------------------------------------------------------------
-  // One step handles one 32-key half hh and consists of M MFMA slots: M1 slots forming S^T of half
-  // hh+1 (phase 1), then M2 slots accumulating O^T += V^T P^T of half hh (phase 2).  A single wave can
-  // hide only a dozen cycles of other instructions under one MFMA and a transcendental costs 16, so
-  // everything else is dealt out evenly, a fixed share behind every MFMA:
-  //   * exp2 / pack / row-sum of half hh in slots [0, EW): one "event" = one exp2 (the second
-  //     event of a logit pair also packs the pair and adds the previous pair to the row sum);
-  //   * LDS fragment reads one batch ahead, one instruction per slot, one wait per batch;
-  //   * SUM_MODE: the test of the row sums against 2^20 right after the last exp event; else the
-  //     row maxima of half hh+1 and the rescale decision in the exp-free tail [RM0, M);
-  //   * in odd steps the workgroup barrier and the ring refill (DMA) in the tail [EW, M).
-  constexpr int M1 = KS * QB;       // MFMAs of phase 1 (K fragment ks feeds QB of them)
-  constexpr int M2 = 2 * DB * QB;   // MFMAs of phase 2 (V^T fragment (tt, db) feeds QB of them)
-  constexpr int M = M1 + M2;
-  constexpr int NP = QB * 8;        // logit pairs per step; pair k: slab k / (4 QB), unit (k / 4) % QB
-  constexpr int NE = 2 * NP;        // exp events
-  constexpr int EW = M1 + M2 / 2;   // events live in slots [0, EW): slab 0 is packed before phase 2,
-                                    // slab 1 before the second half of phase 2 (which reads it)
-  // SUM_MODE: the first NEAR events of a half (all in slab 0) are done EARLY, in the tail slots
-  // [EW, M) of the step before, as soon as its S^T is complete; with them every slot of a step has
-  // the same share of exp2 work.
-  constexpr int NEAR = SUM_MODE ? (NE * (M - EW) / M) & ~1 : 0;
-  constexpr int NMAIN = NE - NEAR;  // events of the half done in its own step, in slots [0, EW)
-  static_assert(NEAR <= NE / 2, "early events must stay inside slab 0");
-  static_assert(NEAR + (M1 * NMAIN + EW - 1) / EW >= NE / 2, "slab 0 would not be complete at the start of phase 2");
-  constexpr int GK = KS / 2;        // K fragments per batch (two batches per step)
-  constexpr int GV = DB;            // V^T fragments per batch (two batches per step, 2 reads each)
-  constexpr int R = 2 * GK + 4 * GV;  // LDS read instructions per step, in issue order:
-                                      //   kg[1] (GK) | vg[0] (2 GV) | vg[1] (2 GV) | kg[0] of the next step (GK)
-  constexpr int RW = EW;            // ... issued in slots [0, RW), evenly
-  static_assert(EW + 1 < M, "no slot for the row-sum test");
-  constexpr int RM1 = M - 1 - QB;  // row-max slots [RM0, RM1), then QB + 1 decision slots
-  constexpr int RM0 = (EW - (M >= 32 ? 2 : 0)) < RM1 ? (EW - (M >= 32 ? 2 : 0)) : RM1 - 1;
-  static_assert(SUM_MODE || RM0 >= M1 + 1, "row maxima would read S^T before its MFMAs retire");
-  static_assert(SUM_MODE || (RM1 > RM0 && RM1 + QB < M), "no room for the row maxima");
-  static_assert(LPG <= (M - EW) * 4, "ring refill does not fit the tail");
-  // read r is issued in slot r * RW / R; main event j >= NEAR in slot (j - NEAR) * EW / NMAIN, early event j < NEAR
-  // of the next half in slot EW + j * (M - EW) / NEAR; reads issued before slot sl:
-  auto rd_before = [](int sl) constexpr { int n = 0; for (int r = 0; r < R; ++r) n += (r * RW / R) < sl; return n; };
+  // ---- the software pipeline (slot schedule: struct Sched) -----------------------------------
+  constexpr int GK = KS / 2, GV = DB;  // fragments per batch, whatever the number of active units
 
   floatx16 sA[QB], sB[QB];
   uintx4 pb[QB][2];      // P^T fragments: 8 bf16 per 16-key slab, as packed pairs
@@ -461,10 +489,12 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   // pairs; the second event of a pair also packs the pair into its P^T slot and the first adds the
   // previous pair's second exp to the row sum (`first`: there is none pending).
   float ev_a = 0.f, ev_b = 0.f;  // first exp of the pair in flight; second exp not yet in its row sum
-  int ev_qb = 0;
-  auto exp_event = [&](const floatx16 (&s)[QB], float (&ls)[QB], int j, bool first) __attribute__((always_inline)) {
-    const int k = j >> 1, slab = k / (QB * 4), kk = k % (QB * 4);
-    const int qb = kk >> 2, jj = kk & 3, r = 8 * slab + 2 * jj;
+  // unit that event j of a step with units Q0 .. QB-1 belongs to
+  auto ev_unit = [](int j, int Q0, int QA) constexpr { return Q0 + (((j >> 1) % (QA * 4)) >> 2); };
+  auto exp_event = [&](const floatx16 (&s)[QB], float (&ls)[QB], int j, bool first, auto q0_tag) __attribute__((always_inline)) {
+    constexpr int Q0 = decltype(q0_tag)::value, QA = QB - Q0;  // active units Q0 .. QB-1
+    const int k = j >> 1, slab = k / (QA * 4), kk = k % (QA * 4);
+    const int qb = Q0 + (kk >> 2), jj = kk & 3, r = 8 * slab + 2 * jj;
     if ((j & 1) == 0) {
       if (first)
         asm volatile("v_exp_f32_e32 %0, %1" : "=v"(ev_a) : "v"(s[qb][r]));
@@ -472,7 +502,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
         asm volatile(
             "v_exp_f32_e32 %0, %2\n\t"
             "v_add_f32_e32 %1, %3, %1"
-            : "=&v"(ev_a), "+v"(ls[ev_qb])
+            : "=&v"(ev_a), "+v"(ls[ev_unit(j - 1, Q0, QA)])
             : "v"(s[qb][r]), "v"(ev_b));
     } else {
       float eb;
@@ -485,17 +515,18 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
           : "v"(s[qb][r + 1]), "v"(ev_a));
       pb[qb][slab][jj] = pku;
       ev_b = eb;
-      ev_qb = qb;
     }
   };
   // the early events of a half all at once (prologue, masked steps, and again after a sum-driven shift)
-  auto early_events = [&](const floatx16 (&s)[QB]) __attribute__((always_inline)) {
+  auto early_events = [&](const floatx16 (&s)[QB], auto q0_tag) __attribute__((always_inline)) {
+    constexpr int Q0 = decltype(q0_tag)::value, QA = QB - Q0;
+    constexpr int NEAR = Sched<D, QA, SUM_MODE, LPG>::NEAR;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) lsum_early[qb] = 0.f;
     if (NEAR > 0) {
 #pragma unroll
-      for (int j = 0; j < NEAR; ++j) exp_event(s, lsum_early, j, j == 0);
-      lsum_early[ev_qb] += ev_b;
+      for (int j = 0; j < NEAR; ++j) exp_event(s, lsum_early, j, j == 0, q0_tag);
+      lsum_early[ev_unit(NEAR - 1, Q0, QA)] += ev_b;
     }
   };
   bf16x8 kg[2][GK];          // K fragment batches
@@ -510,11 +541,17 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   // and the ring refill for the tiles after next; MASKED selects the variant for halves hh+1 that
   // reach past the causal horizon, and for every half once a row sum has overflowed (mask, then the
   // exact row max, after the matrix work); CLAMP the variant whose refill may run past the end of
-  // the cache.
+  // the cache.  q0_tag = 1 (two-unit kernel only): unit 0 has passed its causal horizon for good and
+  // only unit 1 is worked on, with the schedule of a one-unit step; a masked step of both units that
+  // is followed by such a step (next_unit1_only) leaves the early events in that step's numbering.
   auto step = [&](floatx16 (&s_cur)[QB], floatx16 (&s_next)[QB], int hh, auto odd_tag, auto masked_tag,
-                  auto clamp_tag) __attribute__((always_inline)) {
+                  auto clamp_tag, auto q0_tag, bool next_unit1_only = false) __attribute__((always_inline)) {
     constexpr bool ODD = decltype(odd_tag)::value;
     constexpr bool MASKED = decltype(masked_tag)::value;
+    constexpr int Q0 = decltype(q0_tag)::value, QA = QB - Q0;
+    using S = Sched<D, QA, SUM_MODE, LPG>;
+    constexpr int M1 = S::M1, M = S::M, EW = S::EW, NE = S::NE, NEAR = S::NEAR, NMAIN = S::NMAIN, NP = S::NP;
+    constexpr int R = S::R, RW = S::RW, RM0 = S::RM0, RM1 = S::RM1;
     const int t = hh >> 1;
     constexpr int KIMM = ODD ? 0 : HALFB;  // even hh: half hh+1 is the second half of tile t
     constexpr int VIMM = ODD ? HALFB : 0;  // even hh: half hh is the first half of tile t
@@ -523,7 +560,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     for (int qb = 0; qb < QB; ++qb) {
       lsum[qb] = lsum_early[qb];
       lsum_next[qb] = 0.f;
-    }
+    }  // (entries of units before Q0 are carried along untouched and never added anywhere)
     float mx[QB], dm[QB];
     bool need_rescale = false;
     int sum_flag = 0;      // per lane: a row sum of this half passed 2^20 (or is not a number)
@@ -533,9 +570,9 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
 #pragma unroll
     for (int i = 0; i < M; ++i) {
       // ---- waits and the barrier come before the MFMA of the slot
-      if (i == GK * QB) wait_lds<(rd_before(GK * QB) - GK)>();                    // kg[1]
-      if (i == M1) wait_lds<(rd_before(M1) - GK - 2 * GV)>();                     // vg[0]
-      if (i == EW) wait_lds<(rd_before(EW) - GK - 4 * GV)>();                     // vg[1]
+      if (i == GK * QA) wait_lds<(S::rd_before(GK * QA) - GK)>();                 // kg[1]
+      if (i == M1) wait_lds<(S::rd_before(M1) - GK - 2 * GV)>();                  // vg[0]
+      if (i == EW) wait_lds<(S::rd_before(EW) - GK - 4 * GV)>();                  // vg[1]
       if (ODD && i == EW) {
         // Every read of K[t] and V[t] by this wave has returned.  K[t+2] and V[t+1] were issued
         // NV-1 tiles ago: they are the oldest group in flight.
@@ -546,13 +583,13 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       }
       // ---- the MFMA
       if (i < M1) {
-        const int ks = i / QB, qb = i % QB;
+        const int ks = i / QA, qb = Q0 + i % QA;
         if (ks == 0)
           mfma_qk_first(s_next[qb], kg[0][0], qf[qb][0], negm[qb]);
         else
           mfma_qk(s_next[qb], kg[ks / GK][ks % GK], qf[qb][ks]);
       } else {
-        const int sl = (i - M1) / QB, qb = (i - M1) % QB, tt = sl / DB, db = sl % DB;
+        const int sl = (i - M1) / QA, qb = Q0 + (i - M1) % QA, tt = sl / DB, db = sl % DB;
         const short8_ a8 = __builtin_shufflevector(vh[sl / GV][sl % GV][0], vh[sl / GV][sl % GV][1], 0, 1, 2, 3, 4, 5, 6, 7);
         mfma_pv(o[qb][db], __builtin_bit_cast(bf16x8, a8), __builtin_bit_cast(bf16x8, pb[qb][tt]));
       }
@@ -573,43 +610,43 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       }
       // after an even step the next K half starts a new tile: move the K read offsets to its ring
       // slot, a few per slot, between the last read of this tile's K and the first of the next
-      if (!ODD && i >= GK * QB && i < GK * QB + (KS + 1) / 2) {
+      if (!ODD && i >= GK * QA && i < GK * QA + (KS + 1) / 2) {
         const int kn = kslot + 1 == NK ? 0 : kslot + 1;
         const unsigned dk = (unsigned)((kn - kslot) * TILEB);
-        const int a = (i - GK * QB) * 2;
+        const int a = (i - GK * QA) * 2;
         kaddr[a] += dk;
         if (a + 1 < KS) kaddr[a + 1] += dk;
-        if (i == GK * QB + (KS + 1) / 2 - 1) kslot = kn;
+        if (i == GK * QA + (KS + 1) / 2 - 1) kslot = kn;
       }
       // exp events of half hh ...
-      if (i == EW) lsum[ev_qb] += ev_b;
+      if (i == EW) lsum[ev_unit(NE - 1, Q0, QA)] += ev_b;
 #pragma unroll
       for (int j = NEAR + (i * NMAIN + EW - 1) / EW; j < NEAR + ((i + 1) * NMAIN + EW - 1) / EW && j < NE; ++j)
-        exp_event(s_cur, lsum, j, j == NEAR);
+        exp_event(s_cur, lsum, j, j == NEAR, q0_tag);
       // ... and, below the causal horizon, the early ones of half hh+1, whose S^T is complete by now
       if (!MASKED && NEAR > 0 && i >= EW) {
 #pragma unroll
         for (int j = ((i - EW) * NEAR + (M - EW) - 1) / (M - EW); j < ((i - EW + 1) * NEAR + (M - EW) - 1) / (M - EW) && j < NEAR; ++j)
-          exp_event(s_next, lsum_next, j, j == 0);
-        if (i == M - 1) lsum_next[ev_qb] += ev_b;
+          exp_event(s_next, lsum_next, j, j == 0, q0_tag);
+        if (i == M - 1) lsum_next[ev_unit(NEAR - 1, Q0, QA)] += ev_b;
       }
       if (SUM_MODE && i == EW + 1) {
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) sum_flag |= (int)!(lsum[qb] <= kSumThreshold);
+        for (int qb = Q0; qb < QB; ++qb) sum_flag |= (int)!(lsum[qb] <= kSumThreshold);
       }
       // row maxima of half hh+1 (its last MFMA is at least RM0 - M1 slots old), then the decision
       if (!SUM_MODE && !MASKED && i >= RM0 && i < RM1) {
 #pragma unroll
         for (int k = ((i - RM0) * NP) / (RM1 - RM0); k < ((i - RM0 + 1) * NP) / (RM1 - RM0); ++k) {
-          const int q2 = k >> 3, r = 2 * (k & 7);
+          const int q2 = Q0 + (k >> 3), r = 2 * (k & 7);
           if (r == 0)
             mx[q2] = fmaxf(s_next[q2][0], s_next[q2][1]);
           else
             mx[q2] = fmaxf(fmaxf(mx[q2], s_next[q2][r]), s_next[q2][r + 1]);
         }
       }
-      if (!SUM_MODE && !MASKED && i >= RM1 && i < RM1 + QB) dm[i - RM1] = pair_max(mx[i - RM1]);
-      if (!SUM_MODE && !MASKED && i == RM1 + QB) need_rescale = rescale_need(dm);
+      if (!SUM_MODE && !MASKED && i >= RM1 && i < RM1 + QA) dm[Q0 + i - RM1] = pair_max(mx[Q0 + i - RM1]);
+      if (!SUM_MODE && !MASKED && i == RM1 + QA) need_rescale = rescale_need(dm, Q0);
       // ring refill and the V address of the next tile (odd steps, after the barrier)
       if (ODD && i >= EW) {
 #pragma unroll
@@ -628,37 +665,58 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
+    for (int qb = Q0; qb < QB; ++qb) {
       l_run[qb] += lsum[qb];
       lsum_early[qb] = lsum_next[qb];
     }
     if constexpr (SUM_MODE) {
       if (__builtin_expect(__any(sum_flag), 0)) {
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
-        rescale_from_sum(lsum, s_next);
-        if (!MASKED) early_events(s_next);  // they were formed against the old reference: once more
+        for (int qb = Q0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
+        rescale_from_sum(lsum, s_next, Q0);
+        if (!MASKED) early_events(s_next, q0_tag);  // they were formed against the old reference: once more
       }
     }
     if (MASKED) {
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
-      mask_half(s_next, hh + 1);
-      rowmax_all(s_next, mx);
-      need_rescale = rescale_decide(mx, dm);
+      for (int qb = Q0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
+      mask_half(s_next, hh + 1, Q0);
+      rowmax_all(s_next, mx, Q0);
+      need_rescale = rescale_decide(mx, dm, Q0);
     }
     if (__builtin_expect(need_rescale, 0)) {
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
-      rescale_apply(dm, s_next);
+      for (int qb = Q0; qb < QB; ++qb) mfma_settle_v(s_next[qb]);
+      rescale_apply(dm, s_next, Q0);
     }
-    if (MASKED) early_events(s_next);
+    if (MASKED) {
+      if (QB == 2 && Q0 == 0 && next_unit1_only)
+        early_events(s_next, std::integral_constant<int, QB - 1>{});
+      else
+        early_events(s_next, q0_tag);
+    }
   };
 
   if (t_begin < t_end) {
     // A second pass (exact = true) follows only if a row sum overflowed in the first.
     for (bool exact = false;; exact = true) {
       reset_state();
+      // Tiles whose two steps only produce halves entirely below the nearest causal horizon take the
+      // fast variant: step 2t+1 produces half 2t+2 = keys [64t+64, 64t+96), so it needs 64t+96 <= vis_min.
+      int t_fast = (vis_min - 96) / BN + 1;  // first tile that is not fast (vis_min >= 1)
+      if (vis_min < 96 || exact) t_fast = 0;
+      if (t_fast > t_end) t_fast = t_end;
+      // ... and tiles whose refill (tile t + 1 + NV) lies entirely inside the cache need no row clamp
+      int t_nc = (Lm1 + 1) / BN - NV - 1;
+      if (t_nc > t_fast) t_nc = t_fast;
+      // Two-unit kernel: from tile t_dead on every key is beyond the last row of unit 0 and only unit 1
+      // is worked on, fast up to its own horizon (t_fast1), masked from there.
+      int t_dead = (vis_last0 + BN - 1) / BN;
+      if (QB == 1 || exact || t_dead > t_end) t_dead = t_end;
+      int t_fast1 = (vis_first[QB - 1] - 96) / BN + 1;
+      if (vis_first[QB - 1] < 96 || exact) t_fast1 = 0;
+      if (t_fast1 < t_dead) t_fast1 = t_dead;
+      if (t_fast1 > t_end) t_fast1 = t_end;
       unsigned again_zero = 0;  // opaque zero: keeps the prologue's addresses from being computed once and
       asm volatile("" : "+v"(again_zero));  // held in registers across the main loop for the sake of a second pass
       // Prologue.  Steady state at the top of the even step of tile t: K[t], K[t+1], V[t] are in LDS
@@ -693,31 +751,39 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
         float mx[QB], dm[QB];
         rowmax_all(sA, mx);
         if (rescale_decide(mx, dm)) rescale_apply(dm, sA);
-        early_events(sA);
+        if (QB == 2 && t_begin >= t_dead && t_dead < t_end)
+          early_events(sA, std::integral_constant<int, QB - 1>{});  // the first step already works on unit 1 alone
+        else
+          early_events(sA, std::integral_constant<int, 0>{});
         // first K batch of the first step: second half of tile t_begin
 #pragma unroll
         for (int j = 0; j < GK; ++j) kg[0][j] = k_frag(j, HALFB);
       }
-      // Tiles whose two steps only produce halves entirely below the nearest causal horizon take the
-      // fast variant: step 2t+1 produces half 2t+2 = keys [64t+64, 64t+96), so it needs 64t+96 <= vis_min.
-      int t_fast = (vis_min - 96) / BN + 1;  // first tile that is not fast (vis_min >= 1)
-      if (vis_min < 96 || exact) t_fast = 0;
-      if (t_fast > t_end) t_fast = t_end;
-      // ... and tiles whose refill (tile t + 1 + NV) lies entirely inside the cache need no row clamp
-      int t_nc = (Lm1 + 1) / BN - NV - 1;
-      if (t_nc > t_fast) t_nc = t_fast;
       int t = t_begin;
+      constexpr std::integral_constant<int, 0> both{};
       for (; t < t_nc; ++t) {
-        step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::false_type{});
-        step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::false_type{});
+        step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::false_type{}, both);
+        step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::false_type{}, both);
       }
       for (; t < t_fast; ++t) {
-        step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::true_type{});
-        step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::true_type{});
+        step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::true_type{}, both);
+        step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::true_type{}, both);
       }
-      for (; t < t_end; ++t) {
-        step(sA, sB, 2 * t, std::false_type{}, std::true_type{}, std::true_type{});
-        step(sB, sA, 2 * t + 1, std::true_type{}, std::true_type{}, std::true_type{});
+      for (; t < t_dead; ++t) {
+        step(sA, sB, 2 * t, std::false_type{}, std::true_type{}, std::true_type{}, both);
+        step(sB, sA, 2 * t + 1, std::true_type{}, std::true_type{}, std::true_type{}, both, t + 1 == t_dead && t_dead < t_end);
+      }
+      if constexpr (QB == 2) {
+        // unit 0 is done for good (every further key is beyond its last row): unit 1 alone
+        constexpr std::integral_constant<int, 1> second{};
+        for (; t < t_fast1; ++t) {
+          step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::true_type{}, second);
+          step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::true_type{}, second);
+        }
+        for (; t < t_end; ++t) {
+          step(sA, sB, 2 * t, std::false_type{}, std::true_type{}, std::true_type{}, second);
+          step(sB, sA, 2 * t + 1, std::true_type{}, std::true_type{}, std::true_type{}, second);
+        }
       }
       wait_vm<0>();  // nothing of ours may still be writing LDS when the workgroup retires or starts over
       wait_lds<0>();

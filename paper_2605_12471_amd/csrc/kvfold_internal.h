@@ -50,6 +50,7 @@ struct AttnParams {
   int32_t n_wgs;           // Hkv * wgs_per_head * S (the grid is padded to a multiple of 8)
   int32_t pair_order;      // 1: every workgroup is resident at once, two per CU; order them heaviest-first for the
                            // first half and lightest-first for the second so each CU gets a balanced pair
+  int32_t pair_units;      // two-unit bf16 kernel: a wavefront owns an early and a late unit of the chunk (see the kernel)
   float scale_log2e;       // softmax scale * log2(e)
   // Rotary embedding of the queries as they are loaded (nullptr: q is used as handed in): angles of the
   // chunk's absolute positions, [C][d/2] fp32 each

@@ -15,13 +15,15 @@ def H():
     return fold_harness
 
 
-def _run_case(H, oracle, cfg, chunks, splits=0, upw=0, check_lse=True, profile=None, tol=None):
+def _run_case(H, oracle, cfg, chunks, splits=0, upw=0, check_lse=True, profile=None, tol=None, pair=0):
     gpu = H.GpuFold(cfg, capacity=sum(chunks), chunk_tokens=max(chunks))
     oc = H.make_oracle(oracle, cfg, capacity=sum(chunks))
     if splits:
         gpu.cache.set_tuning(0, splits)
     if upw:
         gpu.cache.set_tuning(1, upw)
+    if pair:
+        gpu.cache.set_tuning(2, pair)   # 1 = never, 2 = always pair an early and a late row block in a wavefront
     pos, worst = 0, 0.0
     try:
         for step, C in enumerate(chunks):
@@ -162,3 +164,24 @@ def test_long_prefix_small_case(H, oracle, d, upw):
     clamp-free refill path, on both head dims and both wave shapes."""
     cfg = I.FoldConfig("longish", 22, 1, 8, 2, d, 512, 0, "bf16")
     _run_case(H, oracle, cfg, [512] * 8, upw=upw)
+
+
+@pytest.mark.parametrize("Hq,Hkv,d,chunks", [
+    (8, 2, 128, [256, 256, 100, 256]),        # 4 heads x 8 blocks per KV head: full pairs
+    (28, 4, 128, [160, 33, 160]),             # G = 7: 35 units per head, an odd number (the middle one pairs with itself)
+    (4, 4, 128, [96, 200, 64]),               # G = 1: few units, workgroups partly empty
+    (8, 2, 64, [256, 130, 256]),
+    (6, 3, 128, [32, 31, 1, 64]),             # chunks of one block and less
+])
+@pytest.mark.parametrize("pair", [1, 2])
+def test_unit_pairing(H, oracle, Hq, Hkv, d, chunks, pair):
+    """Two-unit kernel with an early and a late row block per wavefront (and without): the late unit finishes
+    alone once every further key lies beyond the early unit's last row."""
+    cfg = I.FoldConfig("pairing", 23, 1, Hq, Hkv, d, max(chunks), 0, "bf16")
+    _run_case(H, oracle, cfg, chunks, upw=2, pair=pair)
+
+
+@pytest.mark.parametrize("profile", ["step100", "stairs", "late"])
+def test_unit_pairing_with_logit_jumps(H, oracle, profile):
+    cfg = I.FoldConfig("jumps", 15, 1, 8, 2, 128, 256, 0, "bf16")
+    _run_case(H, oracle, cfg, [256, 64, 200], upw=2, check_lse=False, profile=profile, pair=2)
