@@ -197,6 +197,41 @@ def decode_shaped_points(torch, kv, I, dev, L=131072, chunks=(1, 4, 16), reps=20
     return pts
 
 
+def box_peaks(torch, dev):
+    """What this machine delivers on plain library work, measured in the same run, to put the datasheet fractions
+    beside measured ones: a large bf16 GEMM (torch.matmul, 8192^3), a read-only pass over 2 GiB (sum) and a
+    1 GiB copy.  Best of a few repeats each."""
+    def best_ms(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        b = None
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            ms = e0.elapsed_time(e1)
+            b = ms if b is None else min(b, ms)
+        return b
+    n = 8192
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    a = torch.randn((n, n), device=dev, generator=g).bfloat16()
+    b = torch.randn((n, n), device=dev, generator=g).bfloat16()
+    gemm_ms = best_ms(lambda: torch.matmul(a, b))
+    del a, b
+    x = torch.empty(1 << 29, dtype=torch.float32, device=dev).normal_(generator=g)   # 2 GiB
+    read_ms = best_ms(lambda: x.sum())
+    y = torch.empty(1 << 28, dtype=torch.float32, device=dev)                         # 1 GiB
+    copy_ms = best_ms(lambda: y.copy_(x[: 1 << 28]))
+    del x, y
+    torch.cuda.empty_cache()
+    return {"bf16_gemm_8192_tflops": 2.0 * n ** 3 / (gemm_ms * 1e-3) / 1e12,
+            "hbm_read_GBps": (1 << 31) / (read_ms * 1e-3) / 1e9,
+            "hbm_copy_GBps_read_plus_write": 2.0 * (1 << 30) / (copy_ms * 1e-3) / 1e9}
+
+
 def fp32_last_step(torch, kv, I, dev, reps=3):
     """The fp32 correctness mode on the last step of the sweep workload at C=2048 (Hq=28, Hkv=4, d=128, 62K-key
     prefix), against the fp32 MFMA peak.  The prefix rows are seeded N(0,1) written in place."""
@@ -331,6 +366,7 @@ def main():
             w2.close()
         extra["decode_shaped_128k"] = decode_shaped_points(torch, kv, I, dev)
         extra["fp32_mode_sweep_64k_last_step"] = fp32_last_step(torch, kv, I, dev)
+        extra["box_peaks_measured"] = box_peaks(torch, dev)
         # the headline fold with unrotated inputs: rotary embedding applied inside the step
         w3 = Workload(cfg, torch, kv, I, dev, tuning=tuning, rope=True)
         ms3 = time_folds(w3, torch, args.steps, args.warmup)
