@@ -50,6 +50,7 @@ typedef __attribute__((ext_vector_type(4))) short short4_;
 typedef __attribute__((ext_vector_type(8))) short short8_;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 typedef __attribute__((ext_vector_type(4))) unsigned uintx4;
+typedef __attribute__((ext_vector_type(4))) float floatx4;
 
 #define LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(uintptr_t)(p))
 
@@ -208,10 +209,9 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   constexpr int UPW = kUnitsPerWg * QB;        // units per workgroup
   const float sc = p.scale_log2e;
 
-  // ---- my units: Q fragments, pre-multiplied by scale*log2(e), stay in registers for the whole kernel
-  bf16x8 qf[QB][KS];
-  int tok[QB], head[QB];
-  bool store_ok[QB];
+  // ---- my units
+  int tok[QB], head[QB], tokc[QB];
+  bool store_ok[QB], unit_valid[QB];
   int my_vis[QB];     // keys visible to this lane's query row
   int vis_first[QB];  // keys visible to the unit's first row (key blocks entirely below need no mask)
   int vis_last0 = 0;  // keys visible to the last row of unit 0: tiles entirely beyond are dead for it
@@ -228,37 +228,15 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     const int tb = uc / G, hg = uc - tb * G;
     head[qb] = g * G + hg;
     tok[qb] = tb * kRowsPerUnit + m;
-    const int tokc = tok[qb] < C ? tok[qb] : C - 1;
+    tokc[qb] = tok[qb] < C ? tok[qb] : C - 1;
+    unit_valid[qb] = valid;
     store_ok[qb] = valid && (tok[qb] < C);
     if (qb == 0) {
       const int last = tb * kRowsPerUnit + kRowsPerUnit - 1;
       vis_last0 = (int)p.len_prev + (last < C ? last : C - 1) + 1;
     }
-    my_vis[qb] = (int)p.len_prev + tokc + 1;
+    my_vis[qb] = (int)p.len_prev + tokc[qb] + 1;
     vis_first[qb] = (int)p.len_prev + tb * kRowsPerUnit + 1;
-    const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ((int64_t)tokc * Hq + head[qb]) * D;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      bf16x8 raw = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + hi * 8);
-      if (p.rope_cos) {
-        // Rotary embedding at the row's absolute position (Sec. 2), half-split pairs (j, j + D/2), fp32 with
-        // the sine product rounded first, result rounded to bf16: bit for bit what a caller that rotates q
-        // itself and stores it as bf16 would hand in.
-        const bool lower = ks < KS / 2;
-        const int j0 = (lower ? ks : ks - KS / 2) * 16 + hi * 8;  // index of the pair's angle
-        const bf16x8 other = *reinterpret_cast<const bf16x8*>(qrow + (lower ? D / 2 : 0) + j0);
-        const float* cs = p.rope_cos + (int64_t)tokc * (D / 2) + j0;
-        const float* sn = p.rope_sin + (int64_t)tokc * (D / 2) + j0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float t = (float)other[e] * sn[e];
-          raw[e] = (__bf16)__builtin_fmaf((float)raw[e], cs[e], lower ? -t : t);
-        }
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qf[qb][ks][e] = (__bf16)((float)raw[e] * sc);
-      asm volatile("" : "+a"(qf[qb][ks]));  // park the fragment in the AGPR file, where the MFMAs read it
-    }
   }
   const int vis_min = vis_first[0];  // units are ordered by token block, so unit 0 has the nearest horizon
 
@@ -315,6 +293,49 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
 #pragma unroll
     for (int i = 0; i < SLABS; ++i) issue_slab(true, t, t % NV, i, std::true_type{}, extra);
   };
+
+  // ---- the ring is filled first (only addresses are needed), then the Q fragments are fetched: the two
+  // latencies overlap.  Q, pre-multiplied by scale*log2(e), stays in registers for the whole kernel.
+  auto prefill = [&](unsigned extra) __attribute__((always_inline)) {
+    // Steady state at the top of the even step of tile t: K[t], K[t+1], V[t] are in LDS and visible, the
+    // groups {K[t+1+j], V[t+j]}, j = 1 .. NV-1, are in flight.
+    issue_k(t_begin, extra);
+    issue_k(t_begin + 1, extra);
+    issue_v(t_begin, extra);
+#pragma unroll
+    for (int j = 1; j < NV; ++j) {
+      issue_k(t_begin + 1 + j, extra);
+      issue_v(t_begin + j, extra);
+    }
+  };
+  if (t_begin < t_end) prefill(0u);
+  bf16x8 qf[QB][KS];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ((int64_t)tokc[qb] * Hq + head[qb]) * D;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      bf16x8 raw = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + hi * 8);
+      if (p.rope_cos) {
+        // Rotary embedding at the row's absolute position (Sec. 2), half-split pairs (j, j + D/2), fp32 with
+        // the sine product rounded first, result rounded to bf16: bit for bit what a caller that rotates q
+        // itself and stores it as bf16 would hand in.
+        const bool lower = ks < KS / 2;
+        const int j0 = (lower ? ks : ks - KS / 2) * 16 + hi * 8;  // index of the pair's angle
+        const bf16x8 other = *reinterpret_cast<const bf16x8*>(qrow + (lower ? D / 2 : 0) + j0);
+        const float* cs = p.rope_cos + (int64_t)tokc[qb] * (D / 2) + j0;
+        const float* sn = p.rope_sin + (int64_t)tokc[qb] * (D / 2) + j0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float t = (float)other[e] * sn[e];
+          raw[e] = (__bf16)__builtin_fmaf((float)raw[e], cs[e], lower ? -t : t);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[qb][ks][e] = (__bf16)((float)raw[e] * sc);
+      asm volatile("" : "+a"(qf[qb][ks]));  // park the fragment in the AGPR file, where the MFMAs read it
+    }
+  }
 
   // ---- LDS read offsets (per lane) of the tile currently being read, ring slot included; moved
   // from slot to slot once per tile
@@ -717,17 +738,11 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       if (vis_first[QB - 1] < 96 || exact) t_fast1 = 0;
       if (t_fast1 < t_dead) t_fast1 = t_dead;
       if (t_fast1 > t_end) t_fast1 = t_end;
-      unsigned again_zero = 0;  // opaque zero: keeps the prologue's addresses from being computed once and
-      asm volatile("" : "+v"(again_zero));  // held in registers across the main loop for the sake of a second pass
-      // Prologue.  Steady state at the top of the even step of tile t: K[t], K[t+1], V[t] are in LDS
-      // and visible, the groups {K[t+1+j], V[t+j]}, j = 1 .. NV-1, are in flight.
-      issue_k(t_begin, again_zero);
-      issue_k(t_begin + 1, again_zero);
-      issue_v(t_begin, again_zero);
-#pragma unroll
-      for (int j = 1; j < NV; ++j) {
-        issue_k(t_begin + 1 + j, again_zero);
-        issue_v(t_begin + j, again_zero);
+      // Prologue.  The first pass finds the ring filled ahead of the Q loads; a second pass fills it again.
+      if (exact) {
+        unsigned again_zero = 0;  // opaque zero: keeps these addresses from being computed once and held in
+        asm volatile("" : "+v"(again_zero));  // registers across the main loop for the sake of a second pass
+        prefill(again_zero);
       }
       wait_vm<(NV - 1) * LPG>();
       __builtin_amdgcn_s_barrier();
@@ -810,16 +825,20 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     reset_state();
   }
 
-  // ---- epilogue
+  // ---- epilogue.  O^T leaves through LDS (the rings are dead by now): a lane holds four consecutive
+  // columns of one row, which stored directly would be 8- or 16-byte pieces scattered over 32 rows per
+  // instruction; turned in LDS, every store instruction writes whole rows, 16 bytes per lane.
+  __builtin_amdgcn_s_barrier();  // every wavefront of the workgroup is through with the rings
   const int64_t n_rows = (int64_t)C * Hq;
+  constexpr int OROWF = D * 4 + 16;  // padded LDS row: fp32 partials
+  constexpr int OROWH = D * 2 + 16;  // padded LDS row: bf16 output
+  const unsigned obase = lds0 + (unsigned)(w * kRowsPerUnit * OROWF);  // this wavefront's staging area, reused by its units
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const float l_tot = pair_sum(l_run[qb]);
-    if (!store_ok[qb]) continue;
-    const int64_t row = (int64_t)tok[qb] * Hq + head[qb];
+    const int tok0 = tok[qb] - m;  // first token of the unit
     if (p.n_splits == 1) {
       const float inv = 1.f / l_tot;
-      __bf16* orow = reinterpret_cast<__bf16*>(p.out) + row * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -827,23 +846,41 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
           bf16x4 v;
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[qb][db][rg * 4 + e] * inv);
-          *reinterpret_cast<bf16x4*>(orow + db * 32 + 8 * rg + 4 * hi) = v;
+          *LDS_PTR(bf16x4, obase + (unsigned)(m * OROWH + (db * 32 + 8 * rg + 4 * hi) * 2)) = v;
         }
-      if (p.lse && hi == 0)
+      if (p.lse && hi == 0 && store_ok[qb])
         p.lse[(int64_t)head[qb] * C + tok[qb]] = (m_run[qb] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+      constexpr int CPR = D / 8;        // 16-byte chunks per row
+      constexpr int RPI = 64 / CPR;     // rows per store instruction
+#pragma unroll
+      for (int i = 0; i < kRowsPerUnit / RPI; ++i) {
+        const int r = i * RPI + l / CPR, c = l % CPR;
+        const uintx4 x = *LDS_PTR(const uintx4, obase + (unsigned)(r * OROWH + c * 16));
+        if (unit_valid[qb] && tok0 + r < C)
+          *reinterpret_cast<uintx4*>(reinterpret_cast<__bf16*>(p.out) + ((int64_t)(tok0 + r) * Hq + head[qb]) * D + c * 8) = x;
+      }
     } else {
-      float* prow = p.part_o + ((int64_t)split * n_rows + row) * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
-          float4 v = make_float4(o[qb][db][rg * 4 + 0], o[qb][db][rg * 4 + 1], o[qb][db][rg * 4 + 2],
-                                 o[qb][db][rg * 4 + 3]);
-          *reinterpret_cast<float4*>(prow + db * 32 + 8 * rg + 4 * hi) = v;
+          floatx4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = o[qb][db][rg * 4 + e];
+          *LDS_PTR(floatx4, obase + (unsigned)(m * OROWF + (db * 32 + 8 * rg + 4 * hi) * 4)) = v;
         }
-      if (hi == 0) {
+      if (hi == 0 && store_ok[qb]) {
         float2 ml = make_float2(m_run[qb], l_tot);
-        *reinterpret_cast<float2*>(p.part_ml + ((int64_t)split * n_rows + row) * 2) = ml;
+        *reinterpret_cast<float2*>(p.part_ml + ((int64_t)split * n_rows + (int64_t)tok[qb] * Hq + head[qb]) * 2) = ml;
+      }
+      constexpr int CPR = D / 4;        // 16-byte chunks per row
+      constexpr int RPI = 64 / CPR;     // rows per store instruction
+#pragma unroll
+      for (int i = 0; i < kRowsPerUnit / RPI; ++i) {
+        const int r = i * RPI + l / CPR, c = l % CPR;
+        const floatx4 x = *LDS_PTR(const floatx4, obase + (unsigned)(r * OROWF + c * 16));
+        if (unit_valid[qb] && tok0 + r < C)
+          *reinterpret_cast<floatx4*>(p.part_o + ((int64_t)split * n_rows + (int64_t)(tok0 + r) * Hq + head[qb]) * D + c * 4) = x;
       }
     }
   }
