@@ -310,31 +310,42 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   };
   if (t_begin < t_end) prefill(0u);
   bf16x8 qf[QB][KS];
+  {
+    bf16x8 raw[QB][KS];  // every load in flight before the first is waited for
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ((int64_t)tokc[qb] * Hq + head[qb]) * D;
+    for (int qb = 0; qb < QB; ++qb) {
+      const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ((int64_t)tokc[qb] * Hq + head[qb]) * D;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      bf16x8 raw = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + hi * 8);
-      if (p.rope_cos) {
-        // Rotary embedding at the row's absolute position (Sec. 2), half-split pairs (j, j + D/2), fp32 with
-        // the sine product rounded first, result rounded to bf16: bit for bit what a caller that rotates q
-        // itself and stores it as bf16 would hand in.
-        const bool lower = ks < KS / 2;
-        const int j0 = (lower ? ks : ks - KS / 2) * 16 + hi * 8;  // index of the pair's angle
-        const bf16x8 other = *reinterpret_cast<const bf16x8*>(qrow + (lower ? D / 2 : 0) + j0);
-        const float* cs = p.rope_cos + (int64_t)tokc[qb] * (D / 2) + j0;
-        const float* sn = p.rope_sin + (int64_t)tokc[qb] * (D / 2) + j0;
+      for (int ks = 0; ks < KS; ++ks) raw[qb][ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + hi * 8);
+    }
+    if (p.rope_cos) {
+      // Rotary embedding at the row's absolute position (Sec. 2), half-split pairs (j, j + D/2), fp32 with
+      // the sine product rounded first, result rounded to bf16: bit for bit what a caller that rotates q
+      // itself and stores it as bf16 would hand in.  Fragments ks and ks + KS/2 hold the two halves of 8 pairs.
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float t = (float)other[e] * sn[e];
-          raw[e] = (__bf16)__builtin_fmaf((float)raw[e], cs[e], lower ? -t : t);
+      for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+        for (int ks = 0; ks < KS / 2; ++ks) {
+          const float* cs = p.rope_cos + (int64_t)tokc[qb] * (D / 2) + ks * 16 + hi * 8;
+          const float* sn = p.rope_sin + (int64_t)tokc[qb] * (D / 2) + ks * 16 + hi * 8;
+          const bf16x8 lo = raw[qb][ks], up = raw[qb][ks + KS / 2];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float tl = (float)up[e] * sn[e], tu = (float)lo[e] * sn[e];
+            raw[qb][ks][e] = (__bf16)__builtin_fmaf((float)lo[e], cs[e], -tl);
+            raw[qb][ks + KS / 2][e] = (__bf16)__builtin_fmaf((float)up[e], cs[e], tu);
+          }
         }
       }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qf[qb][ks][e] = (__bf16)((float)raw[e] * sc);
-      asm volatile("" : "+a"(qf[qb][ks]));  // park the fragment in the AGPR file, where the MFMAs read it
     }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[qb][ks][e] = (__bf16)((float)raw[qb][ks][e] * sc);
+        asm volatile("" : "+a"(qf[qb][ks]));  // park the fragment in the AGPR file, where the MFMAs read it
+      }
   }
 
   // ---- LDS read offsets (per lane) of the tile currently being read, ring slot included; moved
@@ -439,7 +450,9 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       const float m2 = mine ? fmaxf(m_run[qb], cur + dm[qb]) : m_run[qb];
       const float use = (m2 == -INFINITY) ? 0.f : m2;
       const float delta = use - cur;
-      const float alpha = __builtin_amdgcn_exp2f(-delta);
+      // a row without history (l = 0, O = 0) has nothing to scale, and its first reference may lie far enough
+      // below zero for 2^-delta to overflow
+      const float alpha = (m_run[qb] == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(-delta);
       m_run[qb] = m2;
       l_run[qb] *= alpha;
 #pragma unroll
@@ -453,6 +466,22 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
       }
+    }
+  };
+  // The first half of a pass: no history, so the row max of the half is the reference (0 for a row that sees
+  // none of its keys) and neither l nor O needs touching.
+  auto reference_first = [&](const float (&mx)[QB], floatx16 (&s)[QB]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const float dm = pair_max(mx[qb]);
+      const float use = (dm > -INFINITY) ? dm : 0.f;
+      m_run[qb] = dm;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        negm[qb][r] = -use;
+        s[qb][r] -= use;
+      }
+      asm volatile("" : "+v"(negm[qb]));  // 16 registers from here on, not one value splatted anew ahead of every MFMA chain
     }
   };
   // ls[] holds the row sums of the half just exponentiated (per lane: the 16 keys it owns).  A sum
@@ -763,9 +792,9 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) mfma_settle_v(sA[qb]);
         if (t_begin * BN + 32 > vis_min) mask_half(sA, 2 * t_begin);
-        float mx[QB], dm[QB];
+        float mx[QB];
         rowmax_all(sA, mx);
-        if (rescale_decide(mx, dm)) rescale_apply(dm, sA);
+        reference_first(mx, sA);
         if (QB == 2 && t_begin >= t_dead && t_dead < t_end)
           early_events(sA, std::integral_constant<int, QB - 1>{});  // the first step already works on unit 1 alone
         else

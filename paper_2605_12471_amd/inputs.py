@@ -124,6 +124,7 @@ LOGIT_PROFILES = {
     "stairs": lambda j: 0.5 * j,               # rises by 16 nats every 32 keys, for ever
     "spike": lambda j: 60.0 * (j == 130),      # one dominating key, then back to the floor
     "late": lambda j: 80.0 * (j >= 290),       # the jump lies inside the causal part of the last chunk
+    "deep_start": lambda j: -150.0 * (j < 96),  # the first keys lie 2^216 below the rest: a first reference far below zero
 }
 
 

@@ -91,15 +91,15 @@ def test_units_per_wave_bf16(H, oracle, upw, Hq, Hkv):
 @pytest.mark.parametrize("profile", sorted(I.LOGIT_PROFILES))
 @pytest.mark.parametrize("dtype,upw,splits", [("bf16", 2, 0), ("bf16", 1, 0), ("bf16", 2, 2), ("f32", 0, 0)])
 def test_logit_jumps_and_overflow(H, oracle, profile, dtype, upw, splits):
-    """Logits that jump by 20 ... 100 nats inside the prefix, inside the causal part, or rise without end:
-    the reference of the online softmax has to follow (sum-driven shift, exact second pass after an
-    overflow, exact row max at the causal horizon).  lse is not compared: the steering component of a
+    """Logits that jump by 20 ... 100 nats inside the prefix, inside the causal part, rise without end, or
+    start 150 nats below the rest: the reference of the online softmax has to follow (sum-driven shift, exact
+    second pass after an overflow, exact row max at the causal horizon, a first reference far below zero).  lse is not compared: the steering component of a
     logit of g nats carries a rounding error of g * 2^-9 that is common to all keys (it cancels in out).
     fp32: a logit of g nats is only known to about g * 2^-23 * sqrt(d), and the weights inherit that
     relative error: the 1e-5 of the N(0,1) workloads (|logit| < 10) is scaled with the largest logit."""
     cfg = I.FoldConfig("jumps", 15, 1, 8, 2, 128, 256, 0, dtype)
     chunks = [256, 64, 200]
-    peak = max(I.LOGIT_PROFILES[profile](j) for j in range(sum(chunks)))
+    peak = max(abs(I.LOGIT_PROFILES[profile](j)) for j in range(sum(chunks)))
     _run_case(H, oracle, cfg, chunks, splits=splits, upw=upw, check_lse=False, profile=profile,
               tol=1e-6 * max(10.0, peak) if dtype == "f32" else None)
 
