@@ -267,8 +267,10 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   const unsigned dma_vc = (unsigned)(((l % CH) ^ ((dma_row0 & 3) * VSW)) * 16);
   const unsigned dma_koff = (unsigned)dma_row0 * ROWB + dma_kc;  // lane part of an unclamped offset
   const unsigned dma_voff = (unsigned)dma_row0 * ROWB + dma_vc;
-  // slab i of tile t of K (is_v = false) or V; CLAMP redirects rows past the cache end to the last
-  // valid row (they are masked anyway, but are never read from memory)
+  // slab i of tile t of K (is_v = false) or V; CLAMP redirects rows past the cache end, or past this
+  // workgroup's key range (the ring runs NV + 1 tiles ahead and knows no end), to the last row inside:
+  // they are never used, and so are never fetched from HBM either
+  const unsigned row_lim = (unsigned)(t_end * BN - 1 < Lm1 ? t_end * BN - 1 : Lm1);
   auto issue_slab = [&](bool is_v, int t, int slot, int i, auto clamp_tag, unsigned extra = 0) __attribute__((always_inline)) {
     constexpr bool CLAMP = decltype(clamp_tag)::value;
     const unsigned lds = lds0 + (unsigned)(((is_v ? NK : 0) + slot) * TILEB + (w + 4 * i) * 1024);
@@ -277,7 +279,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       int row0_here = dma_row0;  // opaque copy: what is derived from it is computed here, not once ahead of all
       asm volatile("" : "+v"(row0_here));  // loops and then held in registers through the main loop
       unsigned grow = (unsigned)(t * BN + row0_here + i * 4 * RPS);
-      grow = grow < (unsigned)Lm1 ? grow : (unsigned)Lm1;
+      grow = grow < row_lim ? grow : row_lim;
       off = grow * ROWB + (is_v ? dma_vc : dma_kc) + extra;
       dma16(is_v ? vbase : kbase, off, lds);
     } else {
@@ -756,8 +758,9 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       int t_fast = (vis_min - 96) / BN + 1;  // first tile that is not fast (vis_min >= 1)
       if (vis_min < 96 || exact) t_fast = 0;
       if (t_fast > t_end) t_fast = t_end;
-      // ... and tiles whose refill (tile t + 1 + NV) lies entirely inside the cache need no row clamp
+      // ... and tiles whose refill (tile t + 1 + NV) lies entirely inside the cache and the key range need no row clamp
       int t_nc = (Lm1 + 1) / BN - NV - 1;
+      if (t_nc > t_end - NV - 1) t_nc = t_end - NV - 1;
       if (t_nc > t_fast) t_nc = t_fast;
       // Two-unit kernel: from tile t_dead on every key is beyond the last row of unit 0 and only unit 1
       // is worked on, fast up to its own horizon (t_fast1), masked from there.
