@@ -364,6 +364,22 @@ def main():
                            "algorithmic_GBps": step_bytes(c2, c2.chunk, L) / (t * 1e-3) / 1e9} for L, t in sel],
             }
             w2.close()
+        # config 5: the same 64K tokens folded with every chunk size of the sweep (bf16)
+        sweep = []
+        for C in (128, 512, 2048, 8192):
+            c5 = I.CONFIGS["sweep_64k"].with_(chunk=C)
+            w5 = Workload(c5, torch, kv, I, dev, tuning=tuning)
+            w5.fold()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            w5.fold()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            sweep.append({"C": C, "steps": c5.n_steps, "plan_last_step_workgroups_splits": list(w5.cache.plan(C, c5.total_tokens)),
+                          "fold_ms": dt * 1e3, "tflops": w5.flops / dt / 1e12,
+                          "frac_of_bf16_peak": w5.flops / dt / 1e12 / PEAK_BF16_TFLOPS, "tokens_per_s": c5.total_tokens / dt})
+            w5.close()
+        extra["chunk_size_sweep_64k"] = sweep
         extra["decode_shaped_128k"] = decode_shaped_points(torch, kv, I, dev)
         extra["fp32_mode_sweep_64k_last_step"] = fp32_last_step(torch, kv, I, dev)
         extra["box_peaks_measured"] = box_peaks(torch, dev)

@@ -38,6 +38,10 @@
 //    P is rounded to bf16 by the hardware pack convert; row sums add the unrounded fp32 values.
 //  * Optional split of the key range over workgroups: partial (max, sum, O) go to a workspace
 //    and are merged by the combine kernel.
+//  * Start and end of a workgroup are kept short (they are 4 % of a short-prefix launch): the ring is
+//    filled before the Q rows are fetched, all Q loads are in flight together, the first reference is
+//    set without touching the still-zero O, and the finished O^T is turned in the dead ring space so
+//    that every store instruction writes whole rows.
 #include <type_traits>
 
 #include "kvfold_internal.h"
