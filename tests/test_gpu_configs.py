@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 import torch
 
+import paper_2605_12471_amd as kv
 from paper_2605_12471_amd import inputs as I
 
 pytestmark = pytest.mark.gpu
@@ -183,5 +184,74 @@ def test_decode_shaped_steps_against_128k_cache(H, oracle, C):
         assert np.abs(lse.cpu().double().numpy().T - ref_lse).max() <= 2e-2
         H.assert_cache_bit_exact(gpu, oc)
         print(f"decode-shaped C={C}: max-abs error {err}")
+    finally:
+        gpu.close()
+
+
+def test_largest_cache_of_one_head(H, oracle):
+    """The largest cache one KV head may have (rows x row bytes just under 2^32: 16,777,215 tokens at d=128
+    bf16, 8.6 GB for K and V), a step at its very end.  The oracle cannot walk 16.7M keys per row, so the far
+    prefix is given a closed form: every far K row is the same vector (one logit s_far per query row), far V
+    rows repeat a seeded block of 4099 rows (a prime, so a row offset that wrapped at 2^32 bytes = 2^24 rows
+    would shift the pattern); the queries are steered so that far and near keys weigh about the same.  Then
+        out = (e^s_far * sum_far V + Z_near * out_near) / (N_far e^s_far + Z_near),
+    with out_near and Z_near = exp(lse_near) from the oracle on the last 1000 prefix rows plus the chunk.
+    Checks the 32-bit row offsets at their limit, every far key visited exactly once, the appended rows
+    bit-exact at the end of the buffer and nothing written at its start."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 24 * 2**30:
+        pytest.skip("needs 24 GiB of free device memory")
+    d, Hq, Hkv, C, W, P = 128, 2, 1, 256, 1000, 4099
+    cap = (1 << 24) - 1
+    cfg = I.FoldConfig("largest", 41, 1, Hq, Hkv, d, C, cap, "bf16")
+    n_far = cap - C - W
+    gpu = H.GpuFold(cfg, capacity=cap, chunk_tokens=C)
+    try:
+        qn, kn, vn = I.chunk_qkv(cfg, 0, 0, n_tokens=W, token_base=0)          # near rows
+        q, k, v = I.chunk_qkv(cfg, 0, 1, n_tokens=C, token_base=W)             # the chunk
+        base = I.chunk_qkv(cfg, 0, 2, n_tokens=P, token_base=100000)[2][:, 0].contiguous()   # [P][d] bf16
+        # every query gets a component along a seeded unit vector u and the far key lies against it, so that
+        # s_far is about -7 nats for every row and the 16.7M far keys weigh about as much as the 1256 near ones
+        u = I.chunk_qkv(cfg, 0, 3, n_tokens=1, token_base=200000)[1][0, 0].float()    # (streams are keyed by token index)
+        u = u / u.norm()
+        q = (q.float() + 2.0 * math.sqrt(d) * u).to(torch.bfloat16)
+        kf = (-3.5 * u + 0.05 * I.chunk_qkv(cfg, 0, 4, n_tokens=1, token_base=200001)[1][0, 0].float()).to(torch.bfloat16)  # [d]
+        K, V = gpu.cache.view(0)                                                # [Hkv][cap][d]
+        dev = K.device
+        K[0, :n_far] = kf.to(dev)
+        idx = torch.arange(n_far, device=dev) % P
+        V[0, :n_far] = base.to(dev)[idx]
+        del idx
+        K[0, n_far:n_far + W] = kn[:, 0].to(dev)
+        V[0, n_far:n_far + W] = vn[:, 0].to(dev)
+        head_k, head_v = K[0, :4].clone(), V[0, :4].clone()
+        gpu.cache.set_length(0, cap - C)
+        out, lse = gpu.step(0, q, k, v, want_lse=True)
+        torch.cuda.synchronize()
+        assert gpu.cache.length(0) == cap
+        # appended rows at the very end, bit for bit; the start of the buffer untouched
+        assert np.array_equal(H.bits(K[0, cap - C:]), H.bits(k[:, 0])) and np.array_equal(H.bits(V[0, cap - C:]), H.bits(v[:, 0]))
+        assert torch.equal(K[0, :4], head_k) and torch.equal(V[0, :4], head_v)
+        # near part through the oracle
+        oc = H.make_oracle(oracle, cfg, capacity=W + C)
+        H.oracle_step(oc, qn, kn, vn)
+        out_near, lse_near = H.oracle_step(oc, q, k, v)                         # [C][Hq][d], [C][Hq]
+        # far part in closed form (fp64)
+        s_far = (H.wide(q) @ kf.double().numpy()) / np.sqrt(d)                  # [C][Hq]
+        b64 = base.double().numpy()
+        sum_far_v = (n_far // P) * b64.sum(0) + b64[: n_far % P].sum(0)         # [d]
+        z_near = np.exp(lse_near)
+        den = n_far * np.exp(s_far) + z_near
+        want = (np.exp(s_far)[..., None] * sum_far_v[None, None, :] + z_near[..., None] * out_near) / den[..., None]
+        err = np.abs(H.wide(out) - want).max()
+        print(f"\nlargest cache: {cap} tokens, far weight share {float((n_far * np.exp(s_far) / den).mean()):.3f}, max|out-closed form|={err:.2e}")
+        assert err <= H.TOL["bf16"]
+        share = n_far * np.exp(s_far) / den
+        assert 0.15 < share.mean() < 0.85, "far and near keys should both matter"
+        lerr = np.abs(lse.cpu().double().numpy().T - np.log(den)).max()
+        assert lerr <= 2e-2
+        # one row beyond the end is refused
+        with pytest.raises(kv.KvFoldError):
+            gpu.step(0, q[:1], k[:1], v[:1])
     finally:
         gpu.close()
