@@ -188,11 +188,10 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
 
   // rings: K slots [0, NK), V slots [NK, NK + NV)
 
-  // ---- which workgroup am I (XCD-aware: contiguous logical ranges per XCD)
-  const int per_xcd = gridDim.x / kNumXcd;
-  const int lid = (blockIdx.x % kNumXcd) * per_xcd + blockIdx.x / kNumXcd;
-  if (lid >= p.n_wgs) return;
+  // ---- which workgroup am I (XCD-aware: a KV head stays on its XCDs, see logical_workgroup())
   const int wgs_per_kvh = p.wgs_per_head * p.n_splits;
+  const int lid = logical_workgroup((int)blockIdx.x, (int)gridDim.x, p.n_q_heads / p.group, wgs_per_kvh);
+  if (lid >= p.n_wgs) return;
   const int g = lid / wgs_per_kvh;
   const int rem = lid - g * wgs_per_kvh;
   const int split = rem / p.wgs_per_head;

@@ -33,10 +33,9 @@ __global__ void __launch_bounds__(256, 1) attn_f32_kernel(AttnParams p) {
   unsigned char* sK = smem;
   unsigned char* sV = smem + BN * ROWB;
 
-  const int per_xcd = gridDim.x / kNumXcd;
-  const int lid = (blockIdx.x % kNumXcd) * per_xcd + blockIdx.x / kNumXcd;
-  if (lid >= p.n_wgs) return;
   const int wgs_per_kvh = p.wgs_per_head * p.n_splits;
+  const int lid = logical_workgroup((int)blockIdx.x, (int)gridDim.x, p.n_q_heads / p.group, wgs_per_kvh);
+  if (lid >= p.n_wgs) return;
   const int g = lid / wgs_per_kvh;
   const int rem = lid - g * wgs_per_kvh;
   const int split = rem / p.wgs_per_head;

@@ -6,6 +6,7 @@
 // nothing here synchronises or allocates after kvfold_cache_create.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -75,7 +76,7 @@ size_t bytes_required(const kvfold_config_t* c) {
          (size_t)elem_size(c->dtype);
 }
 
-constexpr int64_t kMaxSplitRows = 1 << 18;  // cap on S * C * Hq rows held in the split workspace
+constexpr int64_t kMaxSplitRows = 1 << 19;  // cap on S * C * Hq rows held in the split workspace
 constexpr int kMaxSplits = 64;
 constexpr int kMinTilesPerSplit = 8;
 
@@ -106,21 +107,32 @@ Plan plan_with(const kvfold_cache* c, int n_tokens, int64_t len_after, int upw) 
   if (c->tune_splits > 0) {
     s = c->tune_splits;
   } else {
-    // Workgroups run in rounds of `slots` (one per CU with two units per wavefront, else two).  Score
-    // a split count by the fill of its last round, a small bonus for more rounds (the dispatcher evens
-    // out unequal workgroups), and the cost of writing and merging s sets of fp32 partials, relative
-    // to the attention work at about 1.1 PFLOP/s and 4 TB/s.
+    // Estimated time of the step for every split count; the smallest wins (by more than 0.5 %).
+    //  * Attention itself at the rate of a full chip (1.35 PFLOP/s, or 5 TB/s for the K and V rows when that
+    //    is longer), divided by what a partly filled last round still delivers.  The chip is power-limited:
+    //    idle CUs hand their share to the busy ones, so 87.5 % of the CUs give 96 % of the rate (measured:
+    //    rate ~ fill^0.3), until the busy CUs reach their top clock (1.41 x the full-chip clock).
+    //  * Unsplit, several rounds, heaviest workgroups first: the slots left over in the last round idle for
+    //    the length of the lightest workgroups only (first token block: the prefix and little else).
+    //  * A residue of imbalance that more rounds even out, 8 us of start and end per round of workgroups,
+    //    and for s > 1 the fp32 partials written and read once at 4 TB/s plus the combine launch.
     const int64_t slots = (int64_t)c->n_cu * (upw == 1 ? 2 : 1);
     const double flops = 4.0 * f.n_q_heads * f.head_dim * (double)n_tokens * ((double)len_after - 0.5 * n_tokens);
-    const double t_attn = flops / 1.1e15 + 2e-6;
-    double best = -1.0;
+    const double kv_bytes = 2.0 * f.n_kv_heads * f.head_dim * (double)elem_size(f.dtype) * (double)len_after;
+    const double t_attn = std::max(flops / 1.35e15, kv_bytes / 5e12);
+    double best = 1e30;
     for (int64_t cand = 1; cand <= s_max; ++cand) {
       const int64_t w = base * cand, rounds = (w + slots - 1) / slots;
-      const double fill = (double)w / (double)(rounds * slots);
-      const double merge = cand > 1 ? ((double)cand * rows * (f.head_dim + 2) * 8.0 / 4e12 + 4e-6) / t_attn : 0.0;
-      const double score = fill * (1.0 - 0.05 / (double)rounds) / (1.0 + merge);
-      if (score > best * 1.005) {
-        best = score;
+      double fill = (double)w / (double)(rounds * slots);
+      if (cand == 1 && rounds >= 2) {
+        const double w_min = (double)(len_after - n_tokens) + kRowsPerUnit, w_mean = (double)len_after - 0.5 * n_tokens;
+        fill = (double)w * w_mean / ((double)w * w_mean + (double)(rounds * slots - w) * w_min);
+      }
+      const double rate = std::min(1.41 * fill, std::pow(fill, 0.3));
+      const double merge = cand > 1 ? (double)cand * rows * (f.head_dim + 2) * 8.0 / 4e12 + 6e-6 : 0.0;
+      const double t = t_attn / rate * (1.0 + 0.03 / (double)rounds) + 8e-6 * (double)rounds + merge;
+      if (t < best * 0.995) {
+        best = t;
         s = cand;
       }
     }

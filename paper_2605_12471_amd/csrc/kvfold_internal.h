@@ -83,5 +83,17 @@ hipError_t launch_combine(const CombineParams& p, hipStream_t s);
 // which keeps the workgroups of one KV head on one XCD's L2.
 constexpr int kNumXcd = 8;
 inline int padded_grid(int n_wgs) { return (n_wgs + kNumXcd - 1) / kNumXcd * kNumXcd; }
+// Logical id (KV head major, then split, then workgroup of the head, heaviest first) of hardware block b.
+// A KV head that spans k = 8 / Hkv XCDs has its workgroups dealt to those XCDs in turn, not in k contiguous
+// runs: every XCD then gets the same mix of heavy and light workgroups and of prefix splits (a contiguous
+// run would put all late token blocks, or a whole split, on one XCD and the light rest on its neighbour).
+__device__ __forceinline__ int logical_workgroup(int b, int grid, int n_kv_heads, int wgs_per_kvh) {
+  const int x = b % kNumXcd, j = b / kNumXcd;
+  if (n_kv_heads < kNumXcd && kNumXcd % n_kv_heads == 0) {
+    const int k = kNumXcd / n_kv_heads;
+    if (wgs_per_kvh % k == 0) return (x / k) * wgs_per_kvh + j * k + x % k;  // grid = Hkv * wgs_per_kvh, a multiple of 8
+  }
+  return x * (grid / kNumXcd) + j;
+}
 
 }  // namespace kvfold
