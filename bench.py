@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0
 # runs of this script (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each scaled by what the same
 # counter reads for the append kernel, a plain copy of known size (write factor 1.000, fetch factor
 # 1.99; summaries under profiles/).  Keyed by (workload, tuning); other combinations report null.
-MEASURED_HBM_TRAFFIC_BYTES = {("llama_16k", ()): 71.6e6, ("full_stack_128k", ()): 612e6}
+MEASURED_HBM_TRAFFIC_BYTES = {("llama_16k", ()): 71.6e6, ("full_stack_128k", ()): 611e6}
 
 
 def step_flops(cfg, C, L_prev):
