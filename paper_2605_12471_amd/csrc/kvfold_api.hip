@@ -150,14 +150,13 @@ Plan choose_plan(const kvfold_cache* c, int n_tokens, int64_t len_after);
 
 Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
   Plan pl = choose_plan(c, n_tokens, len_after);
-  // Two-unit kernel, unsplit, a single round of workgroups: with a prefix shorter than 8 chunks the
-  // causal part makes the last token block's wavefronts 6 % and more longer than the mean and nothing
-  // evens that out; pair an early and a late row block in every wavefront instead (the late one
-  // finishes alone, at the efficiency of a one-unit step: 2-7 % faster on the whole).  With several
-  // rounds the dispatcher balances heaviest-first workgroups by itself and pairing only costs.
+  // Two-unit kernel, unsplit, a single round of workgroups: the causal part makes the last token block's
+  // wavefronts longer than the first's (100 % on an empty cache, 6 % after 8 chunks) and nothing evens that
+  // out; pair an early and a late row block in every wavefront instead (the late one finishes alone, at
+  // the efficiency of a one-unit step).  Measured: +7 % down to +0.5 % at 31 chunks of prefix, even at 63.
+  // With several rounds the dispatcher balances heaviest-first workgroups by itself and pairing only costs.
   if (c->cfg.dtype == KVFOLD_BF16 && pl.units_per_wave == 2 && pl.n_splits == 1 && c->tune_pair_units != 1) {
-    const int64_t len_prev = len_after - n_tokens;
-    if (c->tune_pair_units == 2 || (len_prev < 8 * (int64_t)n_tokens && pl.n_wgs <= c->n_cu)) pl.pair_units = 1;
+    if (c->tune_pair_units == 2 || pl.n_wgs <= c->n_cu) pl.pair_units = 1;
   }
   return pl;
 }
