@@ -199,7 +199,7 @@ int kvfold_cache_set_storage_roundtrip(kvfold_cache_t* cache, int32_t n_bits);
  *                              Clamped to what the split workspace and the key range allow.
  *   KVFOLD_TUNE_UNITS_PER_WAVE 32-row query blocks owned by one wavefront of the bf16 kernel:
  *                              1 or 2; 0 = automatic.
- *   KVFOLD_TUNE_PAIR_UNITS     two-unit kernel, unsplit: each wavefront owns an early and a late row
+ *   KVFOLD_TUNE_PAIR_UNITS     two-unit kernel: each wavefront owns an early and a late row
  *                              block of the chunk (evens out the causal part); 0 = automatic (single
  *                              round of workgroups), 1 = never, 2 = always.
  * Returns KVFOLD_ERR_INVALID_ARG for an unknown knob or a value out of range.  Host-only.

@@ -150,12 +150,13 @@ Plan choose_plan(const kvfold_cache* c, int n_tokens, int64_t len_after);
 
 Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
   Plan pl = choose_plan(c, n_tokens, len_after);
-  // Two-unit kernel, unsplit, a single round of workgroups: the causal part makes the last token block's
-  // wavefronts longer than the first's (100 % on an empty cache, 6 % after 8 chunks) and nothing evens that
-  // out; pair an early and a late row block in every wavefront instead (the late one finishes alone, at
-  // the efficiency of a one-unit step).  Measured: +7 % down to +0.5 % at 31 chunks of prefix, even at 63.
-  // With several rounds the dispatcher balances heaviest-first workgroups by itself and pairing only costs.
-  if (c->cfg.dtype == KVFOLD_BF16 && pl.units_per_wave == 2 && pl.n_splits == 1 && c->tune_pair_units != 1) {
+  // Two-unit kernel, a single round of workgroups: the causal part makes the last token block's wavefronts
+  // longer than the first's (100 % on an empty cache, 6 % after 8 chunks) and nothing evens that out; pair
+  // an early and a late row block in every wavefront instead (the late one finishes alone, at the
+  // efficiency of a one-unit step).  Measured: +7 % down to +0.5 % at 31 chunks of prefix, even at 63; with
+  // a split prefix (only the last pieces hold the causal part) +0.5 to 2 %, never a loss.  With several
+  // rounds the dispatcher balances heaviest-first workgroups by itself and pairing only costs.
+  if (c->cfg.dtype == KVFOLD_BF16 && pl.units_per_wave == 2 && c->tune_pair_units != 1) {
     if (c->tune_pair_units == 2 || pl.n_wgs <= c->n_cu) pl.pair_units = 1;
   }
   return pl;

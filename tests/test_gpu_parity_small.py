@@ -181,6 +181,19 @@ def test_unit_pairing(H, oracle, Hq, Hkv, d, chunks, pair):
     _run_case(H, oracle, cfg, chunks, upw=2, pair=pair)
 
 
+@pytest.mark.parametrize("splits", [2, 3, 5])
+@pytest.mark.parametrize("Hq,Hkv,d,chunks", [
+    (8, 2, 128, [256, 256, 100, 256]),
+    (28, 4, 128, [160, 33, 160]),
+    (4, 2, 64, [96, 300, 64]),
+])
+def test_unit_pairing_with_prefix_splits(H, oracle, Hq, Hkv, d, chunks, splits):
+    """Pairing together with a split key range: pieces that end before the early unit's horizon run both
+    units throughout, pieces that begin beyond it run the late unit alone from their first tile."""
+    cfg = I.FoldConfig("pairsplit", 24, 1, Hq, Hkv, d, max(chunks), 0, "bf16")
+    _run_case(H, oracle, cfg, chunks, splits=splits, upw=2, pair=2)
+
+
 @pytest.mark.parametrize("profile", ["step100", "stairs", "late"])
 def test_unit_pairing_with_logit_jumps(H, oracle, profile):
     cfg = I.FoldConfig("jumps", 15, 1, 8, 2, 128, 256, 0, "bf16")
