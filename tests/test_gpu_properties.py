@@ -93,6 +93,46 @@ def test_determinism_and_stream_order(H):
         assert torch.equal(x, y)
 
 
+@pytest.mark.parametrize("C,L_prev,dtype", [(256, 1024, "bf16"), (16, 4000, "bf16"), (64, 512, "f32")])
+def test_step_under_graph_capture(H, C, L_prev, dtype):
+    """A step allocates nothing and only enqueues kernels, so it can be captured into a HIP graph: several
+    replays, with eager work and synchronisations between them, give the bits of the eager step (unsplit and
+    split launches: append, attention, merge)."""
+    cfg = I.FoldConfig("graph", 25, 1, 8, 2, 128, C, 0, dtype)
+    gpu = H.GpuFold(cfg, capacity=L_prev + C, chunk_tokens=max(C, 256))
+    try:
+        pos = 0
+        while pos < L_prev:                                   # build the prefix eagerly
+            n = min(256, L_prev - pos)
+            q, k, v = I.chunk_qkv(cfg, 0, pos // 256, n_tokens=n, token_base=pos)
+            gpu.step(0, q, k, v)
+            pos += n
+        q, k, v = (t.to(gpu.dev).contiguous() for t in I.chunk_qkv(cfg, 0, 99, n_tokens=C, token_base=L_prev))
+        out = torch.empty_like(q)
+        lse = torch.empty((cfg.n_q_heads, C), dtype=torch.float32, device=gpu.dev)
+        gpu.cache.step(0, q, k, v, out, lse=lse)
+        torch.cuda.synchronize()
+        want, want_lse = out.clone(), lse.clone()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        gpu.cache.set_length(0, L_prev)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                gpu.cache.step(0, q, k, v, out, lse=lse)
+        torch.cuda.synchronize()
+        scratch = torch.empty(1 << 20, device=gpu.dev)
+        for _ in range(4):
+            out.zero_(); lse.zero_()
+            scratch.normal_()                                  # eager work of the program's own in between
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, want) and torch.equal(lse, want_lse)
+        assert gpu.cache.length(0) == L_prev + C
+    finally:
+        gpu.close()
+
+
 @pytest.mark.parametrize("splits,upw", [(1, 1), (1, 2), (3, 1), (4, 2), (7, 1)])
 def test_launch_shape_does_not_change_results_much(H, oracle, splits, upw):
     """Different launch geometries (prefix splits, rows per wave) all match the oracle."""
