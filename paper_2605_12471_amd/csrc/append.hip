@@ -8,21 +8,18 @@
 
 namespace kvfold {
 
-__global__ void __launch_bounds__(256) append_kernel(AppendParams p) {
-  const bool is_v = blockIdx.y != 0;
-  const uint4* __restrict__ src = reinterpret_cast<const uint4*>(is_v ? p.v_new : p.k_new);
-  uint4* __restrict__ dst = reinterpret_cast<uint4*>(is_v ? p.v_cache : p.k_cache);
-  const int64_t vec_per_row = p.row_bytes >> 4;
-  const int64_t per_head = (int64_t)p.n_tokens * vec_per_row;
-  const int64_t total = per_head * p.n_kv_heads;
-  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-       idx += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t g = idx / per_head;
-    const int64_t rem = idx - g * per_head;
-    const int64_t i = rem / vec_per_row;
-    const int64_t c = rem - i * vec_per_row;
-    dst[(g * p.capacity + p.len_prev + i) * vec_per_row + c] = src[(i * p.n_kv_heads + g) * vec_per_row + c];
-  }
+// blockIdx.y = 2 * KV head + (0: K, 1: V).  A row is 8, 16 or 32 16-byte vectors (a power of two), so the
+// (token, vector) split of an index is a shift and a mask, and one head's destination is one contiguous run.
+__global__ void __launch_bounds__(256) append_kernel(AppendParams p, int log2_vpr) {
+  const bool is_v = (blockIdx.y & 1) != 0;
+  const int64_t g = blockIdx.y >> 1;
+  const int64_t vpr = (int64_t)1 << log2_vpr;
+  const uint4* __restrict__ src = reinterpret_cast<const uint4*>(is_v ? p.v_new : p.k_new) + g * vpr;
+  uint4* __restrict__ dst = reinterpret_cast<uint4*>(is_v ? p.v_cache : p.k_cache) + (g * p.capacity + p.len_prev) * vpr;
+  const int64_t per_head = (int64_t)p.n_tokens << log2_vpr;
+  const int64_t src_row = (int64_t)p.n_kv_heads << log2_vpr;  // vectors from one token's row to the next
+  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < per_head; idx += (int64_t)gridDim.x * blockDim.x)
+    dst[idx] = src[(idx >> log2_vpr) * src_row + (idx & (vpr - 1))];
 }
 
 // The same carry with the rotary embedding applied to the K rows on the way (Sec. 2: the new tokens'
@@ -124,11 +121,19 @@ hipError_t launch_storage_roundtrip(const AppendParams& p, int n_bits, hipStream
 hipError_t launch_append(const AppendParams& p, hipStream_t s) {
   const int64_t total = (int64_t)p.n_tokens * p.n_kv_heads * (p.row_bytes >> 4);
   if (total <= 0) return hipSuccess;
+  if (!p.rope_cos) {
+    int log2_vpr = 0;
+    while ((16 << log2_vpr) < p.row_bytes) ++log2_vpr;
+    if ((16 << log2_vpr) != p.row_bytes || p.n_kv_heads > 32767) return hipErrorInvalidValue;
+    const int64_t per_head = (int64_t)p.n_tokens << log2_vpr;
+    int64_t bx = (per_head + 255) / 256;
+    if (bx > 1024) bx = 1024;
+    hipLaunchKernelGGL(append_kernel, dim3((unsigned)bx, (unsigned)(2 * p.n_kv_heads)), dim3(256), 0, s, p, log2_vpr);
+    return hipGetLastError();
+  }
   int64_t blocks = (total + 255) / 256;
   if (blocks > 4096) blocks = 4096;
-  if (!p.rope_cos)
-    hipLaunchKernelGGL(append_kernel, dim3((unsigned)blocks, 2), dim3(256), 0, s, p);
-  else if (p.elem_is_bf16)
+  if (p.elem_is_bf16)
     hipLaunchKernelGGL((append_rope_kernel<__bf16, 8>), dim3((unsigned)blocks, 2), dim3(256), 0, s, p);
   else
     hipLaunchKernelGGL((append_rope_kernel<float, 4>), dim3((unsigned)blocks, 2), dim3(256), 0, s, p);
