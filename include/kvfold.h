@@ -202,9 +202,15 @@ int kvfold_cache_set_storage_roundtrip(kvfold_cache_t* cache, int32_t n_bits);
  *   KVFOLD_TUNE_PAIR_UNITS     two-unit kernel: each wavefront owns an early and a late row
  *                              block of the chunk (evens out the causal part); 0 = automatic (single
  *                              round of workgroups), 1 = never, 2 = always.
+ *   KVFOLD_TUNE_FUSED_APPEND   bf16 mode: the attention kernel copies the chunk's rows into the cache itself
+ *                              (and reads the chunk's own tiles from k_new / v_new) whenever the cache
+ *                              length is a multiple of 64 and neither rotary embedding nor a storage
+ *                              round trip is in play; 0 = automatic, 1 = never (separate append kernel).
+ *                              Either way k_new / v_new must stay valid until the step's work on the
+ *                              stream is done, and the cache ends up with the same bits.
  * Returns KVFOLD_ERR_INVALID_ARG for an unknown knob or a value out of range.  Host-only.
  */
-enum { KVFOLD_TUNE_SPLITS = 0, KVFOLD_TUNE_UNITS_PER_WAVE = 1, KVFOLD_TUNE_PAIR_UNITS = 2 };
+enum { KVFOLD_TUNE_SPLITS = 0, KVFOLD_TUNE_UNITS_PER_WAVE = 1, KVFOLD_TUNE_PAIR_UNITS = 2, KVFOLD_TUNE_FUSED_APPEND = 3 };
 int kvfold_cache_set_tuning(kvfold_cache_t* cache, int32_t knob, int32_t value);
 
 /*

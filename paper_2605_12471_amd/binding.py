@@ -15,6 +15,7 @@ KVFOLD_BF16 = 1
 TUNE_SPLITS = 0
 TUNE_UNITS_PER_WAVE = 1
 TUNE_PAIR_UNITS = 2
+TUNE_FUSED_APPEND = 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("KVFOLD_LIB_PATH") or os.path.join(_HERE, "_lib", "libkvfold.so")

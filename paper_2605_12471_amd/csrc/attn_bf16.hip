@@ -262,6 +262,41 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   const unsigned char* kbase = reinterpret_cast<const unsigned char*>(p.k_cache) + (int64_t)g * p.capacity * ROWB;
   const unsigned char* vbase = reinterpret_cast<const unsigned char*>(p.v_cache) + (int64_t)g * p.capacity * ROWB;
 
+  // ---- fused append (paper Sec. 2: the chunk's K/V rows join the cache): tiles from t_new on lie in the
+  // chunk and are streamed from the rows as handed in, [C][Hkv][d], so no workgroup waits for another's
+  // copy; the copy into the cache, for the steps to come, is shared out over the workgroups of the KV head.
+  const bool fused = p.k_new != nullptr;
+  const unsigned new_stride = (unsigned)(p.n_kv_heads * ROWB);  // bytes from one token's row to the next
+  const unsigned char* knew = reinterpret_cast<const unsigned char*>(p.k_new) + (int64_t)g * ROWB;
+  const unsigned char* vnew = reinterpret_cast<const unsigned char*>(p.v_new) + (int64_t)g * ROWB;
+  // This workgroup's share of the copy: rows [r0, r1) of K and of V, 16 bytes per lane and access.  The first
+  // kCopyFirst vectors per lane are only loaded here and stored once the ring refill and the Q loads are on
+  // their way, so that their latency is not paid on its own; whatever is left (few workgroups, long chunks)
+  // is copied on the spot.
+  constexpr int kCopyFirst = 8;
+  uintx4 copy_v[kCopyFirst];
+  int copy_r0 = 0, copy_nvec = 0;
+  auto copy_src = [&](int idx) __attribute__((always_inline)) -> const uintx4* {
+    const bool is_v = idx >= copy_nvec;
+    const int e = is_v ? idx - copy_nvec : idx, r = copy_r0 + e / CH, c = e % CH;
+    return reinterpret_cast<const uintx4*>((is_v ? vnew : knew) + (int64_t)r * new_stride + c * 16);
+  };
+  auto copy_dst = [&](int idx) __attribute__((always_inline)) -> uintx4* {
+    const bool is_v = idx >= copy_nvec;
+    const int e = is_v ? idx - copy_nvec : idx, r = copy_r0 + e / CH, c = e % CH;
+    return reinterpret_cast<uintx4*>(const_cast<unsigned char*>(is_v ? vbase : kbase) + (p.len_prev + r) * ROWB + c * 16);
+  };
+  if (fused) {
+    const int per = (C + wgs_per_kvh - 1) / wgs_per_kvh;  // rows of this workgroup
+    const int r1 = rem * per + per < C ? rem * per + per : C;
+    copy_r0 = rem * per;
+    copy_nvec = (r1 > copy_r0 ? r1 - copy_r0 : 0) * CH;  // 16-byte vectors per tensor
+#pragma unroll
+    for (int u = 0; u < kCopyFirst; ++u)
+      if (tid + u * 256 < 2 * copy_nvec) copy_v[u] = *copy_src(tid + u * 256);
+    for (int idx = tid + kCopyFirst * 256; idx < 2 * copy_nvec; idx += 256) *copy_dst(idx) = *copy_src(idx);
+  }
+
   // ---- DMA addressing: wavefront w moves slabs w, w+4, ...; lane l lands at chunk (l % CH) of row
   // slab*RPS + l / CH and therefore fetches the chunk that the swizzle maps there.  Offsets from
   // the head's base are 32-bit (the host checks capacity * row bytes < 2^32).
@@ -274,6 +309,11 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   // workgroup's key range (the ring runs NV + 1 tiles ahead and knows no end), to the last row inside:
   // they are never used, and so are never fetched from HBM either
   const unsigned row_lim = (unsigned)(t_end * BN - 1 < Lm1 ? t_end * BN - 1 : Lm1);
+  // Fused append: tiles from t_new on lie in the chunk -- unless this workgroup's key range ends before the
+  // chunk begins: then every row past the range is redirected to row_lim, a cache row, whatever its tile.
+  const bool reaches_chunk = fused && (int64_t)row_lim >= p.len_prev;
+  const int t_new = reaches_chunk ? (int)(p.len_prev / BN) : 0x7fffffff;
+  const unsigned rel_lim = reaches_chunk ? row_lim - (unsigned)p.len_prev : 0u;  // row_lim counted from the chunk's first row
   auto issue_slab = [&](bool is_v, int t, int slot, int i, auto clamp_tag, unsigned extra = 0) __attribute__((always_inline)) {
     constexpr bool CLAMP = decltype(clamp_tag)::value;
     const unsigned lds = lds0 + (unsigned)(((is_v ? NK : 0) + slot) * TILEB + (w + 4 * i) * 1024);
@@ -281,10 +321,14 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     if (CLAMP) {
       int row0_here = dma_row0;  // opaque copy: what is derived from it is computed here, not once ahead of all
       asm volatile("" : "+v"(row0_here));  // loops and then held in registers through the main loop
-      unsigned grow = (unsigned)(t * BN + row0_here + i * 4 * RPS);
-      grow = grow < row_lim ? grow : row_lim;
-      off = grow * ROWB + (is_v ? dma_vc : dma_kc) + extra;
-      dma16(is_v ? vbase : kbase, off, lds);
+      // (wave-uniform choice, scalar selects) a tile of the chunk itself comes from the rows as handed in
+      const bool nw = t >= t_new;
+      const unsigned char* base = nw ? (is_v ? vnew : knew) : (is_v ? vbase : kbase);
+      const unsigned stride = nw ? new_stride : (unsigned)ROWB, lim = nw ? rel_lim : row_lim;
+      unsigned r = (unsigned)((t - (nw ? t_new : 0)) * BN + row0_here + i * 4 * RPS);
+      r = r < lim ? r : lim;
+      off = r * stride + (is_v ? dma_vc : dma_kc) + extra;
+      dma16(base, off, lds);
     } else {
       off = (is_v ? dma_voff : dma_koff) + (unsigned)(t * BN + i * 4 * RPS) * ROWB;
       dma16(is_v ? vbase : kbase, off, lds);
@@ -322,6 +366,11 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ((int64_t)tokc[qb] * Hq + head[qb]) * D;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) raw[qb][ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16 + hi * 8);
+    }
+    if (fused) {
+#pragma unroll
+      for (int u = 0; u < kCopyFirst; ++u)
+        if (tid + u * 256 < 2 * copy_nvec) *copy_dst(tid + u * 256) = copy_v[u];
     }
     if (p.rope_cos) {
       // Rotary embedding at the row's absolute position (Sec. 2), half-split pairs (j, j + D/2), fp32 with
@@ -764,6 +813,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       // ... and tiles whose refill (tile t + 1 + NV) lies entirely inside the cache and the key range need no row clamp
       int t_nc = (Lm1 + 1) / BN - NV - 1;
       if (t_nc > t_end - NV - 1) t_nc = t_end - NV - 1;
+      if (t_nc > t_new - NV - 1) t_nc = t_new - NV - 1;  // ... and inside the cache proper when the append is fused
       if (t_nc > t_fast) t_nc = t_fast;
       // Two-unit kernel: from tile t_dead on every key is beyond the last row of unit 0 and only unit 1
       // is worked on, fast up to its own horizon (t_fast1), masked from there.

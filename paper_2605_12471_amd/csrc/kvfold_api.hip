@@ -32,7 +32,8 @@ struct kvfold_cache {
   std::vector<int64_t> len;
   int tune_splits;
   int tune_units_per_wave;
-  int tune_pair_units;  // 0 automatic, 1 never, 2 whenever the two-unit kernel runs unsplit
+  int tune_pair_units;  // 0 automatic, 1 never, 2 whenever the two-unit kernel runs
+  int tune_fused_append;  // 0 automatic (whenever possible), 1 never: always the separate append kernel
   int storage_bits;  // 0, or 4 / 8: rows are round-tripped through that integer width as they join the cache
   // optional per-kernel timing: 4 events per step (before append, after append, after attention, after merge)
   std::vector<hipEvent_t> prof_events;
@@ -240,6 +241,7 @@ int kvfold_cache_create(const kvfold_config_t* cfg, kvfold_cache_t** out_cache) 
   c->tune_splits = 0;
   c->tune_units_per_wave = 0;
   c->tune_pair_units = 0;
+  c->tune_fused_append = 0;
   c->storage_bits = 0;
   c->len.assign((size_t)cfg->n_layers, 0);
 
@@ -352,6 +354,12 @@ int step_impl(kvfold_cache_t* c, int layer, const void* q, const void* k_new, co
   at.scale_log2e = c->scale * 1.4426950408889634f;
   at.rope_cos = rope_cos;
   at.rope_sin = rope_sin;
+  // The bf16 attention kernel appends by itself when the cache length is a whole number of key tiles (every
+  // chunk length that is a multiple of 64) and nothing has to happen to the rows on their way in.
+  const bool fused_append = f.dtype == KVFOLD_BF16 && !rope_cos && !c->storage_bits && len_prev % kTileKeys == 0 &&
+                            c->tune_fused_append != 1;
+  at.k_new = fused_append ? k_new : nullptr;
+  at.v_new = fused_append ? v_new : nullptr;
   if (pl.n_splits > 1 && (int64_t)pl.n_splits * n_tokens * f.n_q_heads > c->ws_rows) return KVFOLD_ERR_HIP;  // planner bug guard
 
   hipEvent_t* ev = nullptr;
@@ -361,8 +369,10 @@ int step_impl(kvfold_cache_t* c, int layer, const void* q, const void* k_new, co
     e = hipEventRecord(ev[0], s);
     if (e != hipSuccess) return hip_fail(e);
   }
-  e = launch_append(ap, s);
-  if (e != hipSuccess) return hip_fail(e);
+  if (!fused_append) {
+    e = launch_append(ap, s);
+    if (e != hipSuccess) return hip_fail(e);
+  }
   if (c->storage_bits) {
     e = launch_storage_roundtrip(ap, c->storage_bits, s);
     if (e != hipSuccess) return hip_fail(e);
@@ -500,6 +510,10 @@ int kvfold_cache_set_tuning(kvfold_cache_t* c, int32_t knob, int32_t value) {
     case KVFOLD_TUNE_PAIR_UNITS:
       if (value < 0 || value > 2) return KVFOLD_ERR_INVALID_ARG;
       c->tune_pair_units = value;
+      return KVFOLD_OK;
+    case KVFOLD_TUNE_FUSED_APPEND:
+      if (value < 0 || value > 1) return KVFOLD_ERR_INVALID_ARG;
+      c->tune_fused_append = value;
       return KVFOLD_OK;
     case KVFOLD_TUNE_UNITS_PER_WAVE:
       if (value < 0 || value > 2) return KVFOLD_ERR_INVALID_ARG;

@@ -56,6 +56,12 @@ struct AttnParams {
   // chunk's absolute positions, [C][d/2] fp32 each
   const float* rope_cos;
   const float* rope_sin;
+  // Append fused into the bf16 attention kernel (nullptr: the cache already holds the chunk's rows): the
+  // chunk's K / V rows as handed in, [C][Hkv][d].  Requires len_prev to be a multiple of the 64-key tile, so
+  // that a tile lies entirely in the cache or entirely in the chunk.  Tiles of the chunk are then streamed
+  // from here, and every workgroup copies its share of the rows into the cache for the steps to come.
+  const void* k_new;
+  const void* v_new;
 };
 
 struct CombineParams {

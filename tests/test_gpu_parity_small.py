@@ -95,13 +95,14 @@ def test_logit_jumps_and_overflow(H, oracle, profile, dtype, upw, splits):
     start 150 nats below the rest: the reference of the online softmax has to follow (sum-driven shift, exact
     second pass after an overflow, exact row max at the causal horizon, a first reference far below zero).  lse is not compared: the steering component of a
     logit of g nats carries a rounding error of g * 2^-9 that is common to all keys (it cancels in out).
-    fp32: a logit of g nats is only known to about g * 2^-23 * sqrt(d), and the weights inherit that
-    relative error: the 1e-5 of the N(0,1) workloads (|logit| < 10) is scaled with the largest logit."""
+    fp32: a dot product of d fp32 terms that sums to a logit of g nats carries a rounding error of about
+    g * sqrt(d) * 2^-24 nats (7e-7 g at d=128), the weights inherit it as a relative error and the output as
+    that times |v| <= 4: the 1e-5 of the N(0,1) workloads (|logit| < 10) becomes 3e-6 g for these."""
     cfg = I.FoldConfig("jumps", 15, 1, 8, 2, 128, 256, 0, dtype)
     chunks = [256, 64, 200]
     peak = max(abs(I.LOGIT_PROFILES[profile](j)) for j in range(sum(chunks)))
     _run_case(H, oracle, cfg, chunks, splits=splits, upw=upw, check_lse=False, profile=profile,
-              tol=1e-6 * max(10.0, peak) if dtype == "f32" else None)
+              tol=max(1e-5, 3e-6 * peak) if dtype == "f32" else None)
 
 
 def test_isolated_chunk_equals_plain_causal(H, oracle):

@@ -93,6 +93,37 @@ def test_determinism_and_stream_order(H):
         assert torch.equal(x, y)
 
 
+@pytest.mark.parametrize("Hq,Hkv,d,chunks,splits", [
+    (32, 8, 128, [256] * 5, 0),
+    (8, 2, 128, [64, 128, 64, 192, 64], 3),          # split launches: pieces that end before the chunk begins
+    (28, 4, 64, [128, 128, 16, 48, 64, 33, 31, 64], 0),   # lengths that leave and regain a multiple of 64
+    (4, 4, 128, [512, 64, 1, 63, 512], 2),
+])
+def test_fused_append_equals_separate_append(H, Hq, Hkv, d, chunks, splits):
+    """bf16: when the cache length is a multiple of the 64-key tile the attention kernel copies the chunk's rows
+    into the cache itself and reads the chunk's tiles from k_new / v_new; switched off (tuning knob) the
+    separate append kernel runs first.  Same bits either way, outputs and cache."""
+    cfg = I.FoldConfig("fused", 26, 1, Hq, Hkv, d, max(chunks), 0, "bf16")
+    res = []
+    for knob in (0, 1):
+        gpu = H.GpuFold(cfg, capacity=sum(chunks), chunk_tokens=max(chunks))
+        gpu.cache.set_tuning(kv.TUNE_FUSED_APPEND, knob)
+        if splits:
+            gpu.cache.set_tuning(kv.TUNE_SPLITS, splits)
+        outs, pos = [], 0
+        for step, C in enumerate(chunks):
+            q, k, v = I.chunk_qkv(cfg, 0, step, n_tokens=C, token_base=pos)
+            outs.append(gpu.step(0, q, k, v).clone())
+            pos += C
+        torch.cuda.synchronize()
+        K, V = gpu.cache.view(0)
+        res.append((outs, K[:, :pos].clone(), V[:, :pos].clone()))
+        gpu.close()
+    for a, b in zip(res[0][0], res[1][0]):
+        assert torch.equal(a, b)
+    assert torch.equal(res[0][1], res[1][1]) and torch.equal(res[0][2], res[1][2])
+
+
 @pytest.mark.parametrize("C,L_prev,dtype", [(256, 1024, "bf16"), (16, 4000, "bf16"), (64, 512, "f32")])
 def test_step_under_graph_capture(H, C, L_prev, dtype):
     """A step allocates nothing and only enqueues kernels, so it can be captured into a HIP graph: several
