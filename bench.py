@@ -33,7 +33,8 @@ PEAK_HBM_GBS = 8000.0
 # runs of this script (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each scaled by what the same
 # counter reads for the append kernel, a plain copy of known size (write factor 1.000, fetch factor
 # 1.99; summaries under profiles/).  Keyed by (workload, tuning); other combinations report null.
-MEASURED_HBM_TRAFFIC_BYTES = {("llama_16k", ()): 71.6e6, ("full_stack_128k", ()): 611e6}
+MEASURED_HBM_TRAFFIC_BYTES = {("llama_16k", ()): 88.1e6, ("full_stack_128k", ()): 637e6,
+                              ("llama_16k", ((3, 1),)): 71.6e6, ("full_stack_128k", ((3, 1),)): 611e6}
 
 
 def step_flops(cfg, C, L_prev):
@@ -273,6 +274,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--units-per-wave", type=int, default=0)
+    ap.add_argument("--separate-append", action="store_true",
+                    help="run the append as its own kernel (a plain copy of known size: the calibration of the HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
@@ -295,6 +298,8 @@ def main():
         tuning[kv.TUNE_SPLITS] = args.splits
     if args.units_per_wave:
         tuning[kv.TUNE_UNITS_PER_WAVE] = args.units_per_wave
+    if args.separate_append:
+        tuning[kv.TUNE_FUSED_APPEND] = 1
 
     w = Workload(cfg, torch, kv, I, dev, tuning=tuning)
     ms = time_folds(w, torch, args.steps, args.warmup)
