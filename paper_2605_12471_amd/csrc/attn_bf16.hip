@@ -2,8 +2,11 @@
 //
 // What it computes (paper Sec. 2, "KV-Fold"): row i of the chunk, query head h, attends to cache
 // rows j <= len_prev + i of KV head h / G -- the whole prefix plus the causal part of the chunk
-// itself, whose rows the append kernel has already written:
+// itself:
 //     out[i][h] = sum_j softmax_j(scale * q[i][h] . K[j]) V[j].
+// The chunk's rows are either in the cache already (the append kernel ran first) or, when the cache
+// length is a multiple of the key tile, are read from k_new / v_new as handed in while this kernel
+// also copies them into the cache (fused append).
 //
 // Mapping to the machine
 //  * Work unit = (32 consecutive chunk rows, one query head).  A wavefront owns QB units, a

@@ -1,8 +1,9 @@
 // Host side of libkvfold: the C ABI declared in include/kvfold.h.
 //
 // One fold step (paper Sec. 2, "KV-Fold" and "A recurrent view") = validate positions, enqueue
-// the append of the chunk's K/V rows, enqueue chunk-prefix attention over rows [0, len + C), and,
-// when the key range was split over workgroups, enqueue the merge.  Everything is stream-ordered;
+// the append of the chunk's K/V rows (its own kernel, or part of the attention kernel), enqueue
+// chunk-prefix attention over rows [0, len + C), and, when the key range was split over workgroups,
+// enqueue the merge.  Everything is stream-ordered;
 // nothing here synchronises or allocates after kvfold_cache_create.
 #include <hip/hip_runtime.h>
 
