@@ -224,7 +224,8 @@ int kvfold_cache_plan(const kvfold_cache_t* cache, int32_t n_tokens, int64_t len
  * Per-kernel timing for measurements.  Between _begin and _end every step additionally records
  * HIP events on the step's stream around each of its kernels (append, attention, merge), at most
  * `max_steps` steps (further steps run untimed).  _end synchronises the device, adds up the
- * elapsed times in milliseconds, releases the events and returns to normal operation.  Any
+ * elapsed times in milliseconds, releases the events and returns to normal operation.  A step
+ * whose attention kernel appended by itself counts wholly as attention time.  Any
  * output pointer may be NULL.  Event creation makes _begin the only call besides create/destroy
  * that allocates.
  */

@@ -378,7 +378,8 @@ int step_impl(kvfold_cache_t* c, int layer, const void* q, const void* k_new, co
     e = launch_storage_roundtrip(ap, c->storage_bits, s);
     if (e != hipSuccess) return hip_fail(e);
   }
-  if (ev) (void)hipEventRecord(ev[1], s);
+  const bool own_append = !fused_append || c->storage_bits;  // something ran between ev[0] and the attention kernel
+  if (ev && own_append) (void)hipEventRecord(ev[1], s);
   e = (f.dtype == KVFOLD_BF16) ? launch_attn_bf16(at, f.head_dim, pl.units_per_wave, s) : launch_attn_f32(at, f.head_dim, s);
   if (e != hipSuccess) return hip_fail(e);
   if (ev) (void)hipEventRecord(ev[2], s);
@@ -399,7 +400,7 @@ int step_impl(kvfold_cache_t* c, int layer, const void* q, const void* k_new, co
   }
   if (ev) {
     if (pl.n_splits > 1) (void)hipEventRecord(ev[3], s);
-    c->prof_has_merge[(size_t)c->prof_steps] = pl.n_splits > 1;
+    c->prof_has_merge[(size_t)c->prof_steps] = (char)((pl.n_splits > 1 ? 1 : 0) | (own_append ? 2 : 0));
     c->prof_steps++;
   }
   c->len[(size_t)layer] = len_prev + n_tokens;
@@ -567,9 +568,14 @@ int kvfold_cache_profile_end(kvfold_cache_t* c, int32_t* n_steps, double* append
   for (int i = 0; i < c->prof_steps && rc == KVFOLD_OK; ++i) {
     hipEvent_t* ev = &c->prof_events[(size_t)i * 4];
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, ev[0], ev[1]) == hipSuccess) a += ms;
-    if (hipEventElapsedTime(&ms, ev[1], ev[2]) == hipSuccess) t += ms;
-    if (c->prof_has_merge[(size_t)i] && hipEventElapsedTime(&ms, ev[2], ev[3]) == hipSuccess) m += ms;
+    const int flags = c->prof_has_merge[(size_t)i];  // bit 0: a merge kernel ran, bit 1: the append ran as its own kernel
+    if (flags & 2) {
+      if (hipEventElapsedTime(&ms, ev[0], ev[1]) == hipSuccess) a += ms;
+      if (hipEventElapsedTime(&ms, ev[1], ev[2]) == hipSuccess) t += ms;
+    } else if (hipEventElapsedTime(&ms, ev[0], ev[2]) == hipSuccess) {
+      t += ms;  // the attention kernel appended by itself
+    }
+    if ((flags & 1) && hipEventElapsedTime(&ms, ev[2], ev[3]) == hipSuccess) m += ms;
   }
   if (n_steps) *n_steps = c->prof_steps;
   if (append_ms) *append_ms = a;

@@ -315,6 +315,13 @@ def test_plan_and_profile_api(H):
             q, k, v = I.chunk_qkv(cfg, 0, step)
             gpu.step(0, q, k, v)
         n, a, t, m = gpu.cache.profile_end()
-        assert n == 4 and a > 0 and t > 0 and m >= 0
+        assert n == 4 and a == 0 and t > 0 and m >= 0          # lengths are multiples of 64: the attention kernel appends
+        gpu.cache.set_tuning(kv.TUNE_FUSED_APPEND, 1)
+        gpu.cache.profile_begin(2)
+        for step in range(6, 8):
+            q, k, v = I.chunk_qkv(cfg, 0, step)
+            gpu.step(0, q, k, v)
+        n, a, t, m = gpu.cache.profile_end()
+        assert n == 2 and a > 0 and t > 0 and m >= 0           # the append as its own kernel
     finally:
         gpu.close()
