@@ -221,6 +221,16 @@ int kvfold_cache_plan(const kvfold_cache_t* cache, int32_t n_tokens, int64_t len
                       int32_t* n_splits);
 
 /*
+ * The same launch geometry without a cache or a device: what a cache created from `cfg` on a GPU with
+ * `n_compute_units` CUs would use for n_tokens rows at length `len_after`, with every tuning knob at
+ * automatic.  units_per_wave: 32-row query blocks per wavefront (bf16: 1 or 2; fp32: 1).  Host-only,
+ * touches no GPU; output pointers may be NULL.  KVFOLD_ERR_INVALID_ARG / _UNSUPPORTED as for create,
+ * and for n_tokens or len_after outside the configuration.
+ */
+int kvfold_plan_for(const kvfold_config_t* cfg, int32_t n_compute_units, int32_t n_tokens, int64_t len_after,
+                    int32_t* n_workgroups /* host */, int32_t* n_splits /* host */, int32_t* units_per_wave /* host */);
+
+/*
  * Per-kernel timing for measurements.  Between _begin and _end every step additionally records
  * HIP events on the step's stream around each of its kernels (append, attention, merge), at most
  * `max_steps` steps (further steps run untimed).  _end synchronises the device, adds up the

@@ -88,6 +88,9 @@ def load_library() -> ctypes.CDLL:
     lib.kvfold_cache_set_tuning.restype = ctypes.c_int
     lib.kvfold_cache_plan.argtypes = [vp, i32, i64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.kvfold_cache_plan.restype = ctypes.c_int
+    lib.kvfold_plan_for.argtypes = [ctypes.POINTER(kvfold_config_t), i32, i32, i64, ctypes.POINTER(i32), ctypes.POINTER(i32),
+                                    ctypes.POINTER(i32)]
+    lib.kvfold_plan_for.restype = ctypes.c_int
     lib.kvfold_cache_profile_begin.argtypes = [vp, i32]
     lib.kvfold_cache_profile_begin.restype = ctypes.c_int
     dp = ctypes.POINTER(ctypes.c_double)
@@ -174,6 +177,14 @@ def kvfold_cache_plan(cache, n_tokens, len_after):
     w, s = ctypes.c_int32(), ctypes.c_int32()
     rc = load_library().kvfold_cache_plan(cache, n_tokens, len_after, ctypes.byref(w), ctypes.byref(s))
     return rc, w.value, s.value
+
+
+def kvfold_plan_for(cfg, n_compute_units, n_tokens, len_after):
+    """Host-only.  Returns (status, n_workgroups, n_splits, units_per_wave)."""
+    w, s, u = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    rc = load_library().kvfold_plan_for(ctypes.byref(cfg) if cfg is not None else None, n_compute_units, n_tokens, len_after,
+                                        ctypes.byref(w), ctypes.byref(s), ctypes.byref(u))
+    return rc, w.value, s.value, u.value
 
 
 def kvfold_cache_profile_begin(cache, max_steps) -> int:

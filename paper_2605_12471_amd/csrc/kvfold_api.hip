@@ -150,6 +150,15 @@ Plan plan_with(const kvfold_cache* c, int n_tokens, int64_t len_after, int upw) 
 
 Plan choose_plan(const kvfold_cache* c, int n_tokens, int64_t len_after);
 
+// split workspace: room for kMaxSplits pieces of one chunk, capped
+int64_t workspace_rows(const kvfold_config_t* cfg) {
+  const int64_t rows = (int64_t)cfg->chunk_tokens * cfg->n_q_heads;
+  int64_t ws_rows = rows * kMaxSplits;
+  if (ws_rows > kMaxSplitRows) ws_rows = kMaxSplitRows;
+  if (ws_rows < 2 * rows) ws_rows = 0;  // chunks this large never need a split
+  return ws_rows;
+}
+
 Plan make_plan(const kvfold_cache* c, int n_tokens, int64_t len_after) {
   Plan pl = choose_plan(c, n_tokens, len_after);
   // Two-unit kernel, a single round of workgroups: the causal part makes the last token block's wavefronts
@@ -267,11 +276,7 @@ int kvfold_cache_create(const kvfold_config_t* cfg, kvfold_cache_t** out_cache) 
     c->owns_kv = true;
   }
 
-  // split workspace: room for kMaxSplits pieces of one chunk, capped
-  const int64_t rows = (int64_t)cfg->chunk_tokens * cfg->n_q_heads;
-  int64_t ws_rows = rows * kMaxSplits;
-  if (ws_rows > kMaxSplitRows) ws_rows = kMaxSplitRows;
-  if (ws_rows < 2 * rows) ws_rows = 0;  // chunks this large never need a split
+  const int64_t ws_rows = workspace_rows(cfg);
   if (ws_rows > 0) {
     void *po = nullptr, *pm = nullptr;
     e = hipMalloc(&po, (size_t)ws_rows * cfg->head_dim * sizeof(float));
@@ -588,6 +593,25 @@ int kvfold_cache_profile_end(kvfold_cache_t* c, int32_t* n_steps, double* append
   c->prof_max_steps = 0;
   c->prof_steps = 0;
   return rc;
+}
+
+int kvfold_plan_for(const kvfold_config_t* cfg, int32_t n_compute_units, int32_t n_tokens, int64_t len_after,
+                    int32_t* n_workgroups, int32_t* n_splits, int32_t* units_per_wave) {
+  const int rc = validate_config(cfg);
+  if (rc != KVFOLD_OK) return rc;
+  if (n_compute_units < 1 || n_tokens < 1 || n_tokens > cfg->chunk_tokens || len_after < n_tokens ||
+      len_after > cfg->capacity_tokens)
+    return KVFOLD_ERR_INVALID_ARG;
+  kvfold_cache c{};  // host fields only: nothing here touches a device
+  c.cfg = *cfg;
+  c.elem_bytes = elem_size(cfg->dtype);
+  c.ws_rows = workspace_rows(cfg);
+  c.n_cu = n_compute_units;
+  const Plan pl = make_plan(&c, n_tokens, len_after);
+  if (n_workgroups) *n_workgroups = pl.n_wgs;
+  if (n_splits) *n_splits = pl.n_splits;
+  if (units_per_wave) *units_per_wave = pl.units_per_wave;
+  return KVFOLD_OK;
 }
 
 const char* kvfold_status_string(int status) {

@@ -117,6 +117,39 @@ def test_null_handles(lib):
     assert kv.kvfold_cache_profile_end(None)[0] == -1
 
 
+def test_launch_plans_of_the_benchmark_configurations(lib):
+    """The host-side planner on a 256-CU part (no GPU needed): the geometry each benchmark workload is timed in."""
+    def plan(Hq, Hkv, d, C, L, dtype=kv.KVFOLD_BF16, cap=131072):
+        cfg = binding.make_config(1, Hq, Hkv, d, C, cap, dtype)
+        rc, w, s, u = kv.kvfold_plan_for(cfg, 256, C, L)
+        assert rc == 0
+        return w, s, u
+    # config 2 (C=2048 to 16K): first step one unit per wavefront, two workgroups per CU; then one round of 256
+    assert plan(32, 8, 128, 2048, 2048) == (512, 1, 1)
+    for L in (4096, 8192, 16384):
+        assert plan(32, 8, 128, 2048, L) == (256, 1, 2)
+    # config 3 (C=256 to 128K): the prefix is split until the chip is full: 32 workgroups x 8
+    assert plan(32, 8, 128, 256, 131072) == (256, 8, 2)
+    # config 4 (C=4096 to 128K): two rounds of 256, unsplit
+    assert plan(32, 8, 128, 4096, 131072) == (512, 1, 2)
+    # config 5 (G=7, C=2048): 224 busy CUs of 256 beat any split on the power-limited chip
+    assert plan(28, 4, 128, 2048, 65536, cap=65536) == (224, 1, 2)
+    assert plan(28, 4, 128, 8192, 65536, cap=65536) == (1792, 2, 2)
+    # decode-shaped steps against 128K: one unit per wavefront, 512 workgroups (two per CU)
+    w, s, u = plan(32, 8, 128, 16, 131072)
+    assert (w, s, u) == (512, 64, 1)
+    w, s, u = plan(32, 8, 128, 1, 131072)
+    assert u == 1 and 63 <= s <= 64 and w == 8 * s
+    # fp32 mode: one unit per wavefront always
+    assert plan(4, 1, 64, 128, 512, kv.KVFOLD_F32, cap=512)[2] == 1
+    # argument errors
+    cfg = binding.make_config(1, 32, 8, 128, 256, 1024, kv.KVFOLD_BF16)
+    assert kv.kvfold_plan_for(cfg, 256, 257, 1024)[0] == -1      # more rows than the chunk size
+    assert kv.kvfold_plan_for(cfg, 256, 256, 2048)[0] == -1      # beyond the capacity
+    assert kv.kvfold_plan_for(cfg, 0, 256, 1024)[0] == -1
+    assert kv.kvfold_plan_for(None, 256, 256, 1024)[0] == -1
+
+
 def test_status_strings(lib):
     seen = {kv.kvfold_status_string(s) for s in range(0, -8, -1)}
     assert len(seen) == 8 and "unknown status" not in seen
