@@ -255,3 +255,59 @@ def test_largest_cache_of_one_head(H, oracle):
             gpu.step(0, q[:1], k[:1], v[:1])
     finally:
         gpu.close()
+
+
+def test_multi_needle_retrieval_across_chain_depths(H, oracle):
+    """Several needles at once (the paper's multi-needle stress test, Sec. 5, at the operator level): eight key
+    rows planted at seeded positions in eight different chunks of a 32K-token fold (C=512, chain depth 63), each
+    equal to 8 * q/||q|| for its own probing (row, head) of the last chunk.  Every probe has to retrieve its own
+    needle through the carried cache -- the weight argmax, its size against the closed form, the GPU's weight
+    recovered from the kernel's log-sum-exp -- and the probing rows match the oracle."""
+    cfg = I.FoldConfig("multi_needle", 45, 1, 32, 8, 128, 512, 32768, "bf16")
+    N, C, G = cfg.n_steps, cfg.chunk, cfg.n_q_heads // cfg.n_kv_heads
+    last = N - 1
+    rng = np.random.default_rng(20260512)
+    n_needles = 8
+    chunks = [0, 7, 15, 24, 33, 42, 51, 60]                       # one needle per listed chunk
+    kv_heads = rng.permutation(cfg.n_kv_heads)[:n_needles]         # distinct KV heads: the probes do not collide
+    needles = []
+    q_last, _, _ = I.chunk_qkv(cfg, 0, last)
+    for i in range(n_needles):
+        head = int(kv_heads[i]) * G + int(rng.integers(0, G))
+        row = int(rng.integers(0, C))
+        pos = chunks[i] * C + int(rng.integers(0, C))
+        qv = q_last[row, head].float()
+        key = (8.0 * qv / qv.norm()).to(torch.bfloat16)
+        needles.append((pos, row, head, key))
+    gpu = H.GpuFold(cfg)
+    oc = H.make_oracle(oracle, cfg)
+    probe_rows = sorted({r for _, r, _, _ in needles})
+    try:
+        for step in range(N):
+            q, k, v = I.chunk_qkv(cfg, 0, step)
+            k = k.clone()
+            for pos, _, head, key in needles:
+                if pos // C == step:
+                    k[pos - step * C, head // G] = key
+            out, lse = gpu.step(0, q, k, v, want_lse=True)
+            if step < last:
+                H.oracle_step(oc, q, k, v, rows=[0])
+        ref, ref_lse, w = H.oracle_step(oc, q, k, v, rows=probe_rows, want_weights=True)
+        torch.cuda.synchronize()
+        err = np.abs(H.wide(out)[probe_rows] - ref).max()
+        assert err <= H.TOL["bf16"]
+        H.assert_cache_bit_exact(gpu, oc)
+        lse = lse.cpu().double().numpy()                          # [Hq][C]
+        for pos, row, head, key in needles:
+            wi = w[probe_rows.index(row), head]
+            assert int(wi.argmax()) == pos, f"needle at {pos} (chunk {pos // C}) not retrieved by row {row} head {head}"
+            n_keys = last * C + row + 1
+            logit = float(H.wide(q_last)[row, head] @ key.double().numpy()) / math.sqrt(cfg.head_dim)   # 8 |q| / sqrt(d)
+            expect = math.exp(logit) / (math.exp(logit) + n_keys * math.exp(0.5))      # among n logits ~ N(0, 1)
+            assert 0.5 * expect < wi[pos] < 2.0 * expect
+            w_gpu = math.exp(logit - lse[head, row])
+            assert abs(w_gpu - wi[pos]) <= 2e-2 * wi[pos]
+        print(f"\nmulti-needle: 8 needles over chain depth {last}, max|out-oracle| on the probing rows {err:.2e}, "
+              f"weights {[round(float(w[probe_rows.index(r), h][p]), 3) for p, r, h, _ in needles]}")
+    finally:
+        gpu.close()
