@@ -159,6 +159,14 @@ def test_seeded_random_shapes(H, oracle, dtype, Hq, Hkv, d, chunks, splits, upw)
     _run_case(H, oracle, cfg, list(chunks), splits=splits, upw=upw if dtype == "bf16" else 0)
 
 
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("bf16", 48, 24, 128), ("bf16", 64, 64, 64), ("bf16", 10, 5, 128),
+                                             ("bf16", 12, 6, 64), ("f32", 32, 16, 64)])
+def test_more_kv_heads_than_xcds_and_odd_head_counts(H, oracle, dtype, Hq, Hkv, d):
+    """KV head counts above 8 (several heads per XCD) and counts that do not divide 8 (contiguous id ranges)."""
+    cfg = I.FoldConfig("heads", 27, 1, Hq, Hkv, d, 200, 0, dtype)
+    _run_case(H, oracle, cfg, [128, 200, 33, 64])
+
+
 @pytest.mark.parametrize("d,upw", [(64, 2), (64, 1), (128, 2)])
 def test_long_prefix_small_case(H, oracle, d, upw):
     """4K tokens in chunks of 512: enough tiles for the unmasked main loop, the ring to wrap many times and the
