@@ -26,18 +26,34 @@ __global__ void __launch_bounds__(kCombineThreads) combine_kernel(CombineParams 
   float m = -INFINITY, l = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   if (live) {
-    for (int s = sg; s < p.n_splits; s += SG) {
-      const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + ((int64_t)s * p.n_rows + row) * 2);
-      const float4 o = *reinterpret_cast<const float4*>(p.part_o + ((int64_t)s * p.n_rows + row) * p.head_dim + dv * 4);
-      if (ml.y == 0.f) continue;  // this piece saw no visible key for the row
-      const float mn = fmaxf(m, ml.x);
-      const float a = exp2f(m - mn), b = exp2f(ml.x - mn);  // m = -inf the first time: a = 0
-      l = l * a + ml.y * b;
-      acc.x = acc.x * a + o.x * b;
-      acc.y = acc.y * a + o.y * b;
-      acc.z = acc.z * a + o.z * b;
-      acc.w = acc.w * a + o.w * b;
-      m = mn;
+    // pieces in batches of kBatch: all loads of a batch are in flight before the first is folded in
+    constexpr int kBatch = 4;
+    for (int s0 = sg; s0 < p.n_splits; s0 += SG * kBatch) {
+      float2 ml[kBatch];
+      float4 o[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int s = s0 + u * SG;
+        if (s < p.n_splits) {
+          ml[u] = *reinterpret_cast<const float2*>(p.part_ml + ((int64_t)s * p.n_rows + row) * 2);
+          o[u] = *reinterpret_cast<const float4*>(p.part_o + ((int64_t)s * p.n_rows + row) * p.head_dim + dv * 4);
+        } else {
+          ml[u] = make_float2(0.f, 0.f);
+          o[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        if (ml[u].y == 0.f) continue;  // this piece saw no visible key for the row (or lies past the last piece)
+        const float mn = fmaxf(m, ml[u].x);
+        const float a = exp2f(m - mn), b = exp2f(ml[u].x - mn);  // m = -inf the first time: a = 0
+        l = l * a + ml[u].y * b;
+        acc.x = acc.x * a + o[u].x * b;
+        acc.y = acc.y * a + o[u].y * b;
+        acc.z = acc.z * a + o[u].z * b;
+        acc.w = acc.w * a + o[u].w * b;
+        m = mn;
+      }
     }
     red[(rl * SG + sg) * V + dv] = acc;
     if (dv == 0) red_ml[rl * SG + sg] = make_float2(m, l);
