@@ -21,7 +21,7 @@ __device__ __forceinline__ float pair_sum_f(float x) {
 }
 
 template <int D>
-__global__ void __launch_bounds__(256, 1) attn_f32_kernel(AttnParams p) {
+__global__ void __launch_bounds__(256, 2) attn_f32_kernel(AttnParams p) {
   constexpr int CH = D / 4;    // 16-byte chunks per row
   constexpr int ROWB = D * 4;  // bytes per row
   constexpr int BN = kTileKeys;
