@@ -121,9 +121,14 @@ Plan plan_with(const kvfold_cache* c, int n_tokens, int64_t len_after, int upw) 
     const int64_t slots = (int64_t)c->n_cu * (upw == 1 ? 2 : 1);
     const double flops = 4.0 * f.n_q_heads * f.head_dim * (double)n_tokens * ((double)len_after - 0.5 * n_tokens);
     const double kv_bytes = 2.0 * f.n_kv_heads * f.head_dim * (double)elem_size(f.dtype) * (double)len_after;
-    const double t_attn = std::max(flops / 1.35e15, kv_bytes / 5e12);
+    const double t_attn = std::max(flops / (f.dtype == KVFOLD_BF16 ? 1.35e15 : 1.2e14), kv_bytes / 5e12);  // bf16 / fp32 MFMA rates
     double best = 1e30;
     for (int64_t cand = 1; cand <= s_max; ++cand) {
+      // only split counts that whole tiles can realise; the last piece may be shorter than the others, and the
+      // launch lasts as long as the longest
+      const int64_t tps = (ntiles + cand - 1) / cand;
+      if ((ntiles + tps - 1) / tps != cand) continue;
+      const double uneven = (double)(tps * cand) / (double)ntiles;
       const int64_t w = base * cand, rounds = (w + slots - 1) / slots;
       double fill = (double)w / (double)(rounds * slots);
       if (cand == 1 && rounds >= 2) {
@@ -132,7 +137,7 @@ Plan plan_with(const kvfold_cache* c, int n_tokens, int64_t len_after, int upw) 
       }
       const double rate = std::min(1.41 * fill, std::pow(fill, 0.3));
       const double merge = cand > 1 ? (double)cand * rows * (f.head_dim + 2) * 8.0 / 4e12 + 6e-6 : 0.0;
-      const double t = t_attn / rate * (1.0 + 0.03 / (double)rounds) + 8e-6 * (double)rounds + merge;
+      const double t = t_attn * uneven / rate * (1.0 + 0.03 / (double)rounds) + 8e-6 * (double)rounds + merge;
       if (t < best * 0.995) {
         best = t;
         s = cand;
