@@ -274,6 +274,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--units-per-wave", type=int, default=0)
+    ap.add_argument("--decode-shaped-only", action="store_true",
+                    help="run only the decode-shaped points (1..16 tokens against a 128K cache) and print them: for profiling")
     ap.add_argument("--separate-append", action="store_true",
                     help="run the append as its own kernel (a plain copy of known size: the calibration of the HBM counters)")
     args = ap.parse_args()
@@ -292,6 +294,9 @@ def main():
     kv.load_library()  # fails loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.decode_shaped_only:
+        print(json.dumps({"decode_shaped_128k": decode_shaped_points(torch, kv, I, dev)}))
+        return
     cfg = I.CONFIGS[args.workload]
     tuning = {}
     if args.splits:
