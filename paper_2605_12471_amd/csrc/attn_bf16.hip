@@ -131,7 +131,7 @@ constexpr float kRedoThreshold = 1152921504606846976.0f;  // 2^60: beyond this t
 //     [NEAR, NE) in slots [0, EW) of the half's own step, so that slab 0 of P is packed before phase
 //     2 and slab 1 before its second half; with SUM_MODE the first NEAR events (all in slab 0) are
 //     taken EARLY, in the tail slots [EW, M) of the step before, as soon as that S^T is complete;
-//   * LDS fragment reads one batch ahead, in slots [0, RW), one wait per batch;
+//   * LDS fragment reads one batch ahead, in slots [0, RW), RW half way into the tail, one wait per batch;
 //   * SUM_MODE: the test of the row sums against 2^20 right after the last event; else the row
 //     maxima of half hh+1 and the rescale decision in the exp-free tail [RM0, M);
 //   * in odd steps the workgroup barrier and the ring refill (DMA) in the tail [EW, M).
@@ -152,7 +152,7 @@ struct Sched {
   static constexpr int GV = DB;            // V^T fragments per batch (two batches per step, 2 reads each)
   static constexpr int R = 2 * GK + 4 * GV;  // LDS read instructions per step, in issue order:
                                              //   kg[1] (GK) | vg[0] (2 GV) | vg[1] (2 GV) | kg[0] of the next step (GK)
-  static constexpr int RW = EW;
+  static constexpr int RW = EW + (M - EW) / 2;  // (measured: spreading the reads a little into the tail beats stopping at EW)
   static_assert(EW + 1 < M, "no slot for the row-sum test");
   static constexpr int RM1 = M - 1 - QA;   // row-max slots [RM0, RM1), then QA + 1 decision slots
   static constexpr int RM0 = (EW - (M >= 32 ? 2 : 0)) < RM1 ? (EW - (M >= 32 ? 2 : 0)) : RM1 - 1;
