@@ -108,3 +108,33 @@ def test_rope_argument_errors(H):
         assert kv.kvfold_cache_length(h, 0) == 64
     finally:
         g.close()
+
+
+def test_rope_step_at_the_size_of_the_llama_layer(H, oracle):
+    """Benchmark config 2 (Hq=32, Hkv=8, d=128, C=2048 to 16K tokens) through kvfold_step_rope, in the launch
+    configuration bench.py times for its rope-in-step figure: sampled rows of three steps against the oracle
+    (rotation at the absolute positions, then the ordinary fold step), cache bit-exact over all 16K rows."""
+    cfg = I.CONFIGS["llama_16k"]
+    gpu = H.GpuFold(cfg)
+    oc = H.make_oracle(oracle, cfg)
+    worst = 0.0
+    try:
+        for step in range(cfg.n_steps):
+            pos = step * cfg.chunk
+            q, k, v = I.chunk_qkv(cfg, 0, step)
+            cos, sin = I.rope_tables(cfg.head_dim, pos, cfg.chunk)
+            out, lse = gpu.step(0, q, k, v, want_lse=True, rope=(cos, sin))
+            q_bits, q_rot = _rotated(oracle, q, cos, sin, "bf16")
+            k_bits, _ = _rotated(oracle, k, cos, sin, "bf16")
+            rows = I.sample_rows(cfg, step, n_random=20) if step in (0, 3, cfg.n_steps - 1) else [0]
+            ref, ref_lse = oc.step(H.wide(q_rot), k_bits, H.bits(v), oc.len, rows=rows)
+            if len(rows) > 1:
+                torch.cuda.synchronize()
+                err = np.abs(H.wide(out)[rows] - ref).max()
+                worst = max(worst, err)
+                assert err <= H.TOL["bf16"], f"step {step}: max|out-oracle| = {err}"
+                assert np.abs(lse.cpu().double().numpy().T[rows] - ref_lse).max() <= 2e-2
+        H.assert_cache_bit_exact(gpu, oc)
+        print(f"\nrope at config-2 size: worst max-abs error {worst:.2e}")
+    finally:
+        gpu.close()

@@ -45,6 +45,35 @@ def test_roundtrip_cache_bits_and_outputs(H, oracle, n_bits, Hq, Hkv, d, chunks)
         gpu.close()
 
 
+@pytest.mark.parametrize("n_bits", [8, 4])
+def test_roundtrip_at_the_size_of_the_llama_layer(H, oracle, n_bits):
+    """Benchmark config 2 (Hq=32, Hkv=8, d=128, C=2048 to 16K tokens) with the carried cache round-tripped through
+    int8 / int4 at every step: sampled rows of three steps against the oracle's step on the oracle-quantised rows,
+    all 16K cache rows bit-exact."""
+    cfg = I.CONFIGS["llama_16k"]
+    gpu = H.GpuFold(cfg)
+    oc = H.make_oracle(oracle, cfg)
+    gpu.cache.set_storage_roundtrip(n_bits)
+    worst = 0.0
+    try:
+        for step in range(cfg.n_steps):
+            q, k, v = I.chunk_qkv(cfg, 0, step)
+            out = gpu.step(0, q, k, v)
+            kq = oracle.storage_roundtrip(H.bits(k), n_bits)
+            vq = oracle.storage_roundtrip(H.bits(v), n_bits)
+            rows = I.sample_rows(cfg, step, n_random=20) if step in (0, 3, cfg.n_steps - 1) else [0]
+            ref, _ = oc.step(H.wide(q), kq, vq, oc.len, rows=rows)
+            if len(rows) > 1:
+                torch.cuda.synchronize()
+                err = np.abs(H.wide(out)[rows] - ref).max()
+                worst = max(worst, err)
+                assert err <= H.TOL["bf16"], f"step {step}: max|out-oracle| = {err}"
+        H.assert_cache_bit_exact(gpu, oc)
+        print(f"\nint{n_bits} round trip at config-2 size: worst max-abs error {worst:.2e}")
+    finally:
+        gpu.close()
+
+
 def test_roundtrip_switch_and_errors(H):
     cfg = I.FoldConfig("store_sw", 20, 1, 8, 2, 128, 64, 0, "bf16")
     g = H.GpuFold(cfg, capacity=192)
