@@ -400,6 +400,14 @@ def main():
             "ms_per_fold": ms3, "tflops": w3.flops / (ms3 * 1e-3) / 1e12, "ms_per_fold_without": ms,
             "note": "same workload through kvfold_step_rope (q, k_new unrotated; cos/sin tables resident)"}
         w3.close()
+        # ... and with the carried cache round-tripped through int8 at every step (storage perturbation, Sec. 8)
+        w4 = Workload(cfg, torch, kv, I, dev, tuning=tuning)
+        w4.cache.set_storage_roundtrip(8)
+        ms4 = time_folds(w4, torch, args.steps, args.warmup)
+        extra["fold_" + cfg.name + "_int8_roundtrip"] = {
+            "ms_per_fold": ms4, "tflops": w4.flops / (ms4 * 1e-3) / 1e12, "ms_per_fold_without": ms,
+            "note": "rows quantised in place (per-row absmax, bf16 -> int8 -> bf16) by their own kernel after a separate append"}
+        w4.close()
     result["extra"] = extra
     print(json.dumps(result))
 
