@@ -7,8 +7,8 @@
  * to the carried cache, earlier rows are never touched -- Fig. 2, and the
  * recurrence (K^(t),V^(t)) = F((K^(t-1),V^(t-1)), x_t) of "A recurrent view").
  *
- * The method is a reorganisation of ordinary causal attention (Sec. 6,
- * "not a reduction in total memory or FLOPs"), so the oracle is the plain
+ * The method is a reorganisation of ordinary causal attention (Sec. 5 says
+ * so itself: it saves neither memory nor FLOPs in total), so the oracle is the plain
  * definition written out: one dot product per (query row, key), a two-pass
  * softmax over the visible keys, a weighted sum of value rows.  No tiling,
  * no online softmax, no fusion.  Everything is double precision.
@@ -109,6 +109,75 @@ int kvfold_oracle_attend_rows(const double *Kc, const double *Vc, int64_t Hkv,
             if (weights) {
                 double *w = weights + ((size_t)r * Hq + h) * Ltot;
                 for (int64_t j = 0; j < Ltot; ++j) w[j] = (j < n) ? s[j] / l : 0.0;
+            }
+            free(s);
+        }
+    }
+    return fail ? -3 : 0;
+}
+
+/*
+ * The same attention under the mask of the streaming baseline that the paper compares with (Sec. 6,
+ * "Comparison to StreamingLLM": a small number of attention-sink tokens kept from the start of the
+ * sequence plus a sliding window of recent tokens -- 4 sinks + 1020 recent tokens in its experiments --
+ * with position-preserving eviction, i.e. every kept key stays at its original position and nothing is
+ * re-anchored).  Reading taken (the paper gives the cache policy, not a per-row rule): the chunk row at
+ * absolute position p = len_prev + i attends to key j iff
+ *        j <= p   and   ( j < n_sink   or   j > p - window ),
+ * so its own key counts as one of the `window` recent tokens, and a row early enough to see everything
+ * (p < n_sink + window) is an ordinary causal row.  Keys outside the set get weight exactly 0.
+ * Arguments as kvfold_oracle_attend_rows, plus n_sink >= 0 and window >= 1.
+ */
+int kvfold_oracle_attend_rows_window(const double *Kc, const double *Vc, int64_t Hkv,
+                                     int64_t cap, int64_t d, const double *q,
+                                     int64_t C, int64_t Hq, int64_t len_prev,
+                                     double scale, int64_t n_sink, int64_t window,
+                                     const int64_t *rows, int64_t nrows,
+                                     double *out, double *lse, double *weights)
+{
+    if (Hq % Hkv != 0 || len_prev < 0 || len_prev + C > cap) return -1;
+    if (n_sink < 0 || window < 1) return -4;
+    for (int64_t r = 0; r < nrows; ++r)
+        if (rows[r] < 0 || rows[r] >= C) return -2;
+    const int64_t G = Hq / Hkv;
+    const int64_t Ltot = len_prev + C;
+    int fail = 0;
+
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int64_t r = 0; r < nrows; ++r) {
+        for (int64_t h = 0; h < Hq; ++h) {
+            const int64_t i = rows[r];
+            const int64_t g = h / G;
+            const int64_t p = len_prev + i; /* absolute position of the row */
+            const double *qv = q + ((size_t)i * Hq + h) * d;
+            const double *Kg = Kc + (size_t)g * cap * d;
+            const double *Vg = Vc + (size_t)g * cap * d;
+            double *s = (double *)malloc((size_t)(p + 1) * sizeof(double));
+            if (!s) { fail = 1; continue; }
+
+            /* logits of the visible keys and their maximum (the row's own key is always visible) */
+            double m = -INFINITY;
+            for (int64_t j = 0; j <= p; ++j) {
+                const int seen = (j < n_sink) || (j > p - window);
+                if (!seen) { s[j] = -INFINITY; continue; }
+                double acc = 0.0;
+                for (int64_t x = 0; x < d; ++x) acc += qv[x] * Kg[(size_t)j * d + x];
+                s[j] = acc * scale;
+                if (s[j] > m) m = s[j];
+            }
+            double l = 0.0;
+            for (int64_t j = 0; j <= p; ++j) { s[j] = exp(s[j] - m); l += s[j]; } /* exp(-inf) = 0 */
+            double *o = out + ((size_t)r * Hq + h) * d;
+            for (int64_t x = 0; x < d; ++x) o[x] = 0.0;
+            for (int64_t j = 0; j <= p; ++j) {
+                if (s[j] == 0.0) continue;
+                const double w = s[j] / l;
+                for (int64_t x = 0; x < d; ++x) o[x] += w * Vg[(size_t)j * d + x];
+            }
+            if (lse) lse[(size_t)r * Hq + h] = m + log(l);
+            if (weights) {
+                double *w = weights + ((size_t)r * Hq + h) * Ltot;
+                for (int64_t j = 0; j < Ltot; ++j) w[j] = (j <= p) ? s[j] / l : 0.0;
             }
             free(s);
         }

@@ -11,6 +11,8 @@ What it holds
   chunk's K/V rows to a per-layer carried cache, then let the chunk's queries
   attend to every cached row up to and including their own position.  The
   arithmetic is the plain definition, done row by row in ``kvfold_oracle.c``.
+* ``OracleCache.step(..., n_sink=, window=)`` -- the same step under the sink + sliding-window mask of
+  the streaming baseline the paper compares with (Sec. 6), ``kvfold_oracle_attend_rows_window``.
 * :func:`monolithic_causal_attention` -- the paper's FULL condition (Sec. 2,
   "Three reference conditions"): one causal pass over all T tokens, written
   independently in numpy by materialising the T x T masked score matrix.  It
@@ -63,6 +65,9 @@ def _load():
             lib.kvfold_oracle_attend_rows.argtypes = [vp, vp, i64, i64, i64, vp, i64, i64, i64,
                                                       ctypes.c_double, vp, i64, vp, vp, vp]
             lib.kvfold_oracle_attend_rows.restype = ctypes.c_int
+            lib.kvfold_oracle_attend_rows_window.argtypes = [vp, vp, i64, i64, i64, vp, i64, i64, i64,
+                                                             ctypes.c_double, i64, i64, vp, i64, vp, vp, vp]
+            lib.kvfold_oracle_attend_rows_window.restype = ctypes.c_int
             lib.kvfold_oracle_threads.restype = ctypes.c_int
             lib.kvfold_oracle_rope_f32.argtypes = [vp, i64, i64, i64, vp, vp, vp]
             lib.kvfold_oracle_rope_f32.restype = ctypes.c_int
@@ -171,21 +176,24 @@ class OracleCache:
         self.len += C
 
     def step(self, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, pos_offset: int,
-             rows=None, want_weights: bool = False):
+             rows=None, want_weights: bool = False, n_sink: int = 0, window: int | None = None):
         """One fold step. ``q`` is [C][Hq][d] fp64 (already widened by the caller).
 
         ``pos_offset`` must equal the current cache length (positions continue
         from tC, Sec. 2).  ``rows`` selects chunk rows to evaluate (default all).
         Returns (out [nrows][Hq][d], lse [nrows][Hq]) and, if asked, the softmax
-        weights [nrows][Hq][len_after].
+        weights [nrows][Hq][len_after].  ``window`` (with ``n_sink``) selects the sink + sliding-window
+        mask of the streaming baseline (Sec. 6): the append is the same, the row at absolute position p
+        attends to keys j < n_sink and p - window < j <= p only.
         """
         if pos_offset != self.len:
             raise ValueError(f"pos_offset {pos_offset} != cache length {self.len}")
         len_prev = self.len
         self.append(k_new, v_new)
-        return self.attend(q, len_prev, rows, want_weights)
+        return self.attend(q, len_prev, rows, want_weights, n_sink, window)
 
-    def attend(self, q: np.ndarray, len_prev: int, rows=None, want_weights: bool = False):
+    def attend(self, q: np.ndarray, len_prev: int, rows=None, want_weights: bool = False,
+               n_sink: int = 0, window: int | None = None):
         """Attention of chunk rows against the cache that already holds the chunk."""
         lib = _load()
         q = np.ascontiguousarray(q, np.float64)
@@ -196,20 +204,26 @@ class OracleCache:
         out = np.empty((n, self.Hq, self.d), np.float64)
         lse = np.empty((n, self.Hq), np.float64)
         w = np.empty((n, self.Hq, len_prev + C), np.float64) if want_weights else None
-        rc = lib.kvfold_oracle_attend_rows(_ptr(self.K), _ptr(self.V), self.Hkv, self.cap, self.d, _ptr(q),
-                                           C, self.Hq, len_prev, self.scale, _ptr(rows), n,
-                                           _ptr(out), _ptr(lse), _ptr(w) if want_weights else None)
+        if window is None:
+            rc = lib.kvfold_oracle_attend_rows(_ptr(self.K), _ptr(self.V), self.Hkv, self.cap, self.d, _ptr(q),
+                                               C, self.Hq, len_prev, self.scale, _ptr(rows), n,
+                                               _ptr(out), _ptr(lse), _ptr(w) if want_weights else None)
+        else:
+            rc = lib.kvfold_oracle_attend_rows_window(_ptr(self.K), _ptr(self.V), self.Hkv, self.cap, self.d, _ptr(q),
+                                                      C, self.Hq, len_prev, self.scale, int(n_sink), int(window),
+                                                      _ptr(rows), n, _ptr(out), _ptr(lse),
+                                                      _ptr(w) if want_weights else None)
         if rc:
             raise ValueError(f"oracle attend failed rc={rc}")
         return (out, lse, w) if want_weights else (out, lse)
 
 
 def fold(Q: np.ndarray, K: np.ndarray, V: np.ndarray, chunk_sizes, n_kv_heads: int | None = None,
-         scale: float | None = None):
+         scale: float | None = None, n_sink: int = 0, window: int | None = None):
     """Left fold over chunks (Sec. 2: foldl(F, (empty, empty), [x_0 .. x_{N-1}])).
 
     Q [T][Hq][d], K/V [T][Hkv][d] fp64; ``chunk_sizes`` sums to T.  Returns
-    (out [T][Hq][d], lse [T][Hq]).
+    (out [T][Hq][d], lse [T][Hq]).  ``window`` / ``n_sink``: every step under the sink + sliding-window mask.
     """
     T, Hq, d = Q.shape
     Hkv = K.shape[1] if n_kv_heads is None else n_kv_heads
@@ -217,7 +231,7 @@ def fold(Q: np.ndarray, K: np.ndarray, V: np.ndarray, chunk_sizes, n_kv_heads: i
     cache = OracleCache(Hq, Hkv, d, T, scale)
     outs, lses, pos = [], [], 0
     for C in chunk_sizes:
-        o, l = cache.step(Q[pos:pos + C], K[pos:pos + C], V[pos:pos + C], pos)
+        o, l = cache.step(Q[pos:pos + C], K[pos:pos + C], V[pos:pos + C], pos, n_sink=n_sink, window=window)
         outs.append(o)
         lses.append(l)
         pos += C

@@ -390,3 +390,130 @@ def test_storage_roundtrip_small_case_by_hand(oracle):
     x = np.array([[127.0, 63.5, -0.5, 2.4]], np.float32)                          # int8, scale 1: 127, 64, -0, 2
     y = oracle.bf16_bits_to_f32(oracle.storage_roundtrip(oracle.f32_to_bf16_bits(x), 8))
     assert np.array_equal(y, np.array([[127.0, 64.0, -0.0, 2.0]], np.float32))
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Sink + sliding-window leg (Sec. 6, the streaming baseline's mask: n_sink first keys + the last `window`
+# keys, positions preserved): the row at absolute position p sees j < n_sink and p - window < j <= p.
+# ---------------------------------------------------------------------------------------------------------
+def _brute_window(Q, K, V, scale, n_sink, window):
+    """Pure python loops over the visible set, nothing vectorised."""
+    T, Hq, d = Q.shape
+    G = Hq // K.shape[1]
+    out = np.zeros((T, Hq, d))
+    for p in range(T):
+        seen = [j for j in range(p + 1) if j < n_sink or j > p - window]
+        for h in range(Hq):
+            g = h // G
+            s = [scale * sum(Q[p, h, x] * K[j, g, x] for x in range(d)) for j in seen]
+            m = max(s)
+            e = [math.exp(v - m) for v in s]
+            l = sum(e)
+            for a, j in enumerate(seen):
+                for x in range(d):
+                    out[p, h, x] += e[a] / l * V[j, g, x]
+    return out
+
+
+def _window_mask(T, n_sink, window):
+    i = np.arange(T)[:, None]
+    j = np.arange(T)[None, :]
+    return (j <= i) & ((j < n_sink) | (j > i - window))
+
+
+@pytest.mark.parametrize("n_sink,window", [(0, 1), (0, 4), (2, 3), (4, 5), (1, 30), (3, 1)])
+def test_window_brute_force_tiny(oracle, n_sink, window):
+    T, Hq, Hkv, d = 14, 4, 2, 8
+    Q, K, V = _rand(T, Hq, Hkv, d, 21)
+    ref = _brute_window(Q, K, V, 1 / math.sqrt(d), n_sink, window)
+    for chunks in ([T], [1] * T, [5, 9], [3, 3, 3, 5]):
+        out, _ = oracle.fold(Q, K, V, chunks, n_sink=n_sink, window=window)
+        assert np.abs(out - ref).max() < 1e-13, (chunks, n_sink, window)
+
+
+@pytest.mark.parametrize("T,Hq,Hkv,d,n_sink,window", [(200, 4, 2, 16, 4, 20), (257, 8, 2, 32, 0, 64), (130, 6, 3, 8, 7, 1),
+                                                      (96, 4, 1, 64, 4, 1020)])
+def test_window_matches_torch_sdpa_with_explicit_mask(oracle, T, Hq, Hkv, d, n_sink, window):
+    Q, K, V = _rand(T, Hq, Hkv, d, 22)
+    G = Hq // Hkv
+    mask = torch.from_numpy(_window_mask(T, n_sink, window))
+    q = torch.from_numpy(Q).permute(1, 0, 2)[None]
+    k = torch.from_numpy(K).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    v = torch.from_numpy(V).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=mask)[0].permute(1, 0, 2).numpy()
+    for chunks in ([T], [64] * (T // 64) + ([T % 64] if T % 64 else []), [T - 1, 1]):
+        out, lse = oracle.fold(Q, K, V, chunks, n_sink=n_sink, window=window)
+        assert np.abs(out - ref).max() < 1e-12
+    # log-sum-exp over exactly the visible keys
+    S = np.einsum("ihx,jhx->hij", Q, np.repeat(K, G, axis=1)) / math.sqrt(d)
+    S = np.where(_window_mask(T, n_sink, window)[None], S, -np.inf)
+    want = np.log(np.exp(S - S.max(-1, keepdims=True)).sum(-1)) + S.max(-1)
+    assert np.abs(lse - want.T).max() < 1e-12
+
+
+def test_window_that_covers_everything_is_the_plain_step(oracle):
+    """window >= length: no key is hidden, and the result is the plain step's bit for bit."""
+    T, Hq, Hkv, d = 150, 4, 2, 16
+    Q, K, V = _rand(T, Hq, Hkv, d, 23)
+    plain, plain_lse = oracle.fold(Q, K, V, [50, 50, 50])
+    for n_sink, window in ((0, T), (0, 10 * T), (5, T), (T, 1), (T + 7, 3)):      # sinks alone can cover everything too
+        out, lse = oracle.fold(Q, K, V, [50, 50, 50], n_sink=n_sink, window=window)
+        assert np.array_equal(out, plain) and np.array_equal(lse, plain_lse), (n_sink, window)
+
+
+def test_window_weights_live_on_the_visible_set_only(oracle):
+    T, Hq, Hkv, d, n_sink, window = 90, 4, 2, 8, 3, 11
+    Q, K, V = _rand(T, Hq, Hkv, d, 24)
+    oc = oracle.OracleCache(Hq, Hkv, d, T)
+    oc.step(Q[:40], K[:40], V[:40], 0)
+    out, lse, w = oc.step(Q[40:], K[40:], V[40:], 40, want_weights=True, n_sink=n_sink, window=window)
+    mask = _window_mask(T, n_sink, window)[40:]                                   # [50][T]
+    assert np.all(w[:, :, :][~np.broadcast_to(mask[:, None, :], w.shape)] == 0.0)  # exactly zero outside
+    assert np.all(w[np.broadcast_to(mask[:, None, :], w.shape)] > 0.0)
+    assert np.abs(w.sum(-1) - 1).max() < 1e-14
+    assert (mask.sum(-1) == n_sink + window).all()                                # 3 sinks + 11 recent keys per row
+    G = Hq // Hkv
+    assert np.abs(np.einsum("rhj,jhx->rhx", w, np.repeat(V, G, axis=1)) - out).max() < 1e-13
+
+
+def test_window_closed_forms(oracle):
+    T, Hq, Hkv, d = 120, 4, 2, 8
+    Q, K, V = _rand(T, Hq, Hkv, d, 25)
+    # window 1, no sinks: every row sees its own key only
+    out, lse = oracle.fold(Q, K, V, [40, 80], n_sink=0, window=1)
+    G = Hq // Hkv
+    assert np.array_equal(out, np.repeat(V, G, axis=1))
+    s_own = np.einsum("ihx,ihx->ih", Q, np.repeat(K, G, axis=1)) / math.sqrt(d)
+    assert np.abs(lse - s_own).max() < 1e-13
+    # all keys equal: uniform weights over the visible set -> mean of the visible V rows
+    Kc = np.broadcast_to(K[:1], K.shape).copy()
+    n_sink, window = 2, 9
+    out, lse = oracle.fold(Q, Kc, V, [30, 30, 60], n_sink=n_sink, window=window)
+    mask = _window_mask(T, n_sink, window)
+    want = (mask[:, :, None, None] * V[None]).sum(1) / mask.sum(1)[:, None, None]  # [T][Hkv][d]
+    assert np.abs(out - np.repeat(want, G, axis=1)).max() < 1e-13
+
+
+def test_window_pins_discriminate_planted_mistakes(oracle):
+    """Plausible mistakes in the visibility rule move the result by far more than the pins' tolerances."""
+    T, Hq, Hkv, d, n_sink, window = 80, 4, 2, 8, 4, 10
+    Q, K, V = _rand(T, Hq, Hkv, d, 26)
+    good, _ = oracle.fold(Q, K, V, [T], n_sink=n_sink, window=window)
+    wrong_rules = {
+        "window one key too long": lambda i, j: (j <= i) & ((j < n_sink) | (j >= i - window)),
+        "window one key too short": lambda i, j: (j <= i) & ((j < n_sink) | (j > i - window + 1)),
+        "sinks forgotten": lambda i, j: (j <= i) & (j > i - window),
+        "one sink too many": lambda i, j: (j <= i) & ((j <= n_sink) | (j > i - window)),
+        "window counted from the chunk end, not the row": lambda i, j: (j <= i) & ((j < n_sink) | (j > T - 1 - window)),
+    }
+    G = Hq // Hkv
+    i = np.arange(T)[:, None]
+    j = np.arange(T)[None, :]
+    for name, rule in wrong_rules.items():
+        mask = rule(i, j)
+        S = np.einsum("ihx,jhx->hij", Q, np.repeat(K, G, axis=1)) / math.sqrt(d)
+        S = np.where(mask[None], S, -np.inf)
+        P = np.exp(S - S.max(-1, keepdims=True))
+        P /= P.sum(-1, keepdims=True)
+        bad = np.einsum("hij,jhx->ihx", P, np.repeat(V, G, axis=1))
+        assert np.abs(bad - good).max() > 1e-3, name
