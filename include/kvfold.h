@@ -11,8 +11,13 @@
  * (Sec. 2), which this interface expresses as `pos_offset`.
  *
  * All entry points are plain C, return an `int` status (0 = KVFOLD_OK,
- * negative = error), never throw, never print and never abort.  On any error
- * nothing has been enqueued and the cache state is unchanged.
+ * negative = error), never throw, never print and never abort.  Every error
+ * except KVFOLD_ERR_HIP is found before anything is enqueued: nothing has run
+ * and the cache is unchanged.  KVFOLD_ERR_HIP from a step means the HIP runtime
+ * refused a launch (everything a valid configuration could be refused for is
+ * settled by kvfold_cache_create): the layer's length is unchanged, but
+ * kernels of that step launched before the failure stay enqueued and rows
+ * [length, length + n_tokens) of the layer may have been written.
  *
  * Pointer kinds are stated per argument: "host" pointers are ordinary process
  * memory, "device" pointers are HIP device allocations on the cache's device.
@@ -52,7 +57,7 @@ typedef struct {
   uint32_t struct_size;    /* must be sizeof(kvfold_config_t)                                 */
   int32_t n_layers;        /* independent per-layer caches, >= 1                              */
   int32_t n_q_heads;       /* Hq, multiple of n_kv_heads                                      */
-  int32_t n_kv_heads;      /* Hkv >= 1                                                        */
+  int32_t n_kv_heads;      /* Hkv, 1 .. 32767                                                 */
   int32_t head_dim;        /* d: 64 or 128                                                    */
   int32_t chunk_tokens;    /* C used by kvfold_step(); also the largest n_tokens of _ex; >= 1 */
   int64_t capacity_tokens; /* rows reserved per layer; the cache grows in place up to this    */
@@ -120,10 +125,11 @@ int kvfold_step_ex(kvfold_cache_t* cache, int layer, const void* q, const void* 
 /*
  * Same step for callers that hold q and k_new UNROTATED: the rotary position
  * embedding of the new tokens at their absolute positions pos_offset + i is
- * applied inside the step ("Position identifiers for the new tokens are
- * continued from the absolute sequence position", Sec. 2) -- to the K rows as
- * they are appended (the cache holds rotated keys, as a model's cache does) and
- * to the queries as the attention kernel loads them; V is untouched.
+ * applied inside the step (Sec. 2: the position ids of chunk t go on from the
+ * absolute position tC, which keeps the rotations aligned with the unchunked
+ * sequence) -- to the K rows as they are appended (the cache holds rotated
+ * keys, as a model's cache does) and to the queries as the attention kernel
+ * loads them; V is untouched.
  *   rope_cos, rope_sin  device, [n_tokens][head_dim/2] float, 16-byte aligned:
  *        cosine and sine of the angle of pair j at row i's absolute position
  *        (what a model's rotary cache holds for positions pos_offset ..
@@ -140,6 +146,23 @@ int kvfold_step_ex(kvfold_cache_t* cache, int layer, const void* q, const void* 
 int kvfold_step_rope(kvfold_cache_t* cache, int layer, const void* q, const void* k_new, const void* v_new,
                      int32_t n_tokens, int64_t pos_offset, const float* rope_cos, const float* rope_sin, void* out,
                      float* lse, void* stream);
+
+/*
+ * The same step under the mask of the streaming baseline the paper compares with (Sec. 6, "Comparison to
+ * StreamingLLM": a few attention-sink tokens kept from the start of the sequence plus a sliding window of
+ * recent tokens, 4 + 1020 in its experiments, evicted keys losing their place but kept ones keeping their
+ * original positions).  The chunk's rows are appended exactly as in kvfold_step_ex (the cache stays complete,
+ * so plain and windowed steps can be mixed on one cache), but the row at absolute position p = pos_offset + i
+ * attends only to the keys
+ *        j < n_sink   or   p - window < j <= p
+ * (its own key is one of the `window` recent ones).  n_sink >= 0, 1 <= window <= 2^30, else
+ * KVFOLD_ERR_INVALID_ARG; a window that covers the whole cache gives the result of kvfold_step_ex.  Work and
+ * HBM reads are proportional to n_sink + window, not to the cache length: key tiles between the sinks and the
+ * window are never touched.  All other arguments, layouts and errors as kvfold_step_ex.
+ */
+int kvfold_step_window(kvfold_cache_t* cache, int layer, const void* q, const void* k_new, const void* v_new,
+                       int32_t n_tokens, int64_t pos_offset, int32_t n_sink, int64_t window, void* out, float* lse,
+                       void* stream);
 
 /*
  * Destroy a cache: synchronises the device, frees library-owned memory (never
@@ -164,7 +187,7 @@ int kvfold_cache_view(const kvfold_cache_t* cache, int layer, void** k_dev, void
  * Rewind `layer` (-1 = every layer) to `new_len` rows, 0 = reset.  Shrink only:
  * new_len must not exceed the current length of the layer (of any layer when
  * layer is -1), else KVFOLD_ERR_POSITION and nothing changes.  Rows stay in HBM;
- * the cache accumulates and never overwrites (Sec. 3.3), so re-running the
+ * the cache accumulates and never overwrites (Sec. 3), so re-running the
  * steps after a rewind re-appends identical rows.  Host-only; the caller orders
  * it against in-flight steps.
  */
@@ -204,8 +227,10 @@ int kvfold_cache_set_storage_roundtrip(kvfold_cache_t* cache, int32_t n_bits);
  *                              round of workgroups), 1 = never, 2 = always.
  *   KVFOLD_TUNE_FUSED_APPEND   bf16 mode: the attention kernel copies the chunk's rows into the cache itself
  *                              (and reads the chunk's own tiles from k_new / v_new) whenever the cache
- *                              length is a multiple of 64 and neither rotary embedding nor a storage
- *                              round trip is in play; 0 = automatic, 1 = never (separate append kernel).
+ *                              length is a multiple of 64, neither rotary embedding nor a storage
+ *                              round trip is in play, and n_tokens * n_kv_heads * head_dim * 2 bytes is
+ *                              below 2^32 (the kernel addresses the chunk with 32-bit byte offsets; larger
+ *                              chunks go through the separate append kernel); 0 = automatic, 1 = never.
  *                              Either way k_new / v_new must stay valid until the step's work on the
  *                              stream is done, and the cache ends up with the same bits.
  * Returns KVFOLD_ERR_INVALID_ARG for an unknown knob or a value out of range.  Host-only.
@@ -222,13 +247,22 @@ int kvfold_cache_plan(const kvfold_cache_t* cache, int32_t n_tokens, int64_t len
 
 /*
  * The same launch geometry without a cache or a device: what a cache created from `cfg` on a GPU with
- * `n_compute_units` CUs would use for n_tokens rows at length `len_after`, with every tuning knob at
- * automatic.  units_per_wave: 32-row query blocks per wavefront (bf16: 1 or 2; fp32: 1).  Host-only,
- * touches no GPU; output pointers may be NULL.  KVFOLD_ERR_INVALID_ARG / _UNSUPPORTED as for create,
- * and for n_tokens or len_after outside the configuration.
+ * `n_compute_units` CUs would use for a step of n_tokens rows that leaves the cache at `len_after` rows, with
+ * every tuning knob at automatic; window > 0 asks for the sink + sliding-window step (kvfold_step_window),
+ * window = 0 for the plain one.  Host-only, touches no GPU.  KVFOLD_ERR_INVALID_ARG / _UNSUPPORTED as for
+ * create, and for n_tokens, len_after, n_sink or window outside the configuration, or out == NULL.
  */
-int kvfold_plan_for(const kvfold_config_t* cfg, int32_t n_compute_units, int32_t n_tokens, int64_t len_after,
-                    int32_t* n_workgroups /* host */, int32_t* n_splits /* host */, int32_t* units_per_wave /* host */);
+typedef struct {
+  int32_t n_workgroups;    /* workgroups of the attention kernel                                        */
+  int32_t n_splits;        /* pieces the key range is cut into (> 1: a merge kernel follows)            */
+  int32_t units_per_wave;  /* 32-row query blocks per wavefront (bf16: 1 or 2; fp32: 1)                 */
+  int32_t tiles_per_split; /* 64-key tiles per piece                                                    */
+  int32_t fused_append;    /* 1: the attention kernel appends the chunk's rows itself (kvfold_step_ex)  */
+  int32_t pair_units;      /* 1: every wavefront owns an early and a late row block of the chunk        */
+  int32_t pair_order;      /* 1: workgroups ordered so that each CU gets a heavy and a light one        */
+} kvfold_plan_t;
+int kvfold_plan_for(const kvfold_config_t* cfg /* host */, int32_t n_compute_units, int32_t n_tokens, int64_t len_after,
+                    int32_t n_sink, int64_t window, kvfold_plan_t* out /* host */);
 
 /*
  * Per-kernel timing for measurements.  Between _begin and _end every step additionally records

@@ -39,6 +39,11 @@ class kvfold_config_t(ctypes.Structure):
     ]
 
 
+class kvfold_plan_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_workgroups", "n_splits", "units_per_wave", "tiles_per_split",
+                                              "fused_append", "pair_units", "pair_order")]
+
+
 class KvFoldError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -71,6 +76,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvfold_step_ex.restype = ctypes.c_int
     lib.kvfold_step_rope.argtypes = [vp, ctypes.c_int, vp, vp, vp, i32, i64, vp, vp, vp, vp, vp]
     lib.kvfold_step_rope.restype = ctypes.c_int
+    lib.kvfold_step_window.argtypes = [vp, ctypes.c_int, vp, vp, vp, i32, i64, i32, i64, vp, vp, vp]
+    lib.kvfold_step_window.restype = ctypes.c_int
     lib.kvfold_cache_destroy.argtypes = [vp]
     lib.kvfold_cache_destroy.restype = ctypes.c_int
     lib.kvfold_cache_length.argtypes = [vp, ctypes.c_int]
@@ -88,8 +95,7 @@ def load_library() -> ctypes.CDLL:
     lib.kvfold_cache_set_tuning.restype = ctypes.c_int
     lib.kvfold_cache_plan.argtypes = [vp, i32, i64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.kvfold_cache_plan.restype = ctypes.c_int
-    lib.kvfold_plan_for.argtypes = [ctypes.POINTER(kvfold_config_t), i32, i32, i64, ctypes.POINTER(i32), ctypes.POINTER(i32),
-                                    ctypes.POINTER(i32)]
+    lib.kvfold_plan_for.argtypes = [ctypes.POINTER(kvfold_config_t), i32, i32, i64, i32, i64, ctypes.POINTER(kvfold_plan_t)]
     lib.kvfold_plan_for.restype = ctypes.c_int
     lib.kvfold_cache_profile_begin.argtypes = [vp, i32]
     lib.kvfold_cache_profile_begin.restype = ctypes.c_int
@@ -139,6 +145,11 @@ def kvfold_step_rope(cache, layer, q, k_new, v_new, n_tokens, pos_offset, rope_c
                                            out, lse, stream)
 
 
+def kvfold_step_window(cache, layer, q, k_new, v_new, n_tokens, pos_offset, n_sink, window, out, lse=None, stream=0) -> int:
+    return load_library().kvfold_step_window(cache, layer, q, k_new, v_new, n_tokens, pos_offset, n_sink, window,
+                                             out, lse, stream)
+
+
 def kvfold_cache_destroy(cache) -> int:
     return load_library().kvfold_cache_destroy(cache)
 
@@ -179,12 +190,12 @@ def kvfold_cache_plan(cache, n_tokens, len_after):
     return rc, w.value, s.value
 
 
-def kvfold_plan_for(cfg, n_compute_units, n_tokens, len_after):
-    """Host-only.  Returns (status, n_workgroups, n_splits, units_per_wave)."""
-    w, s, u = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+def kvfold_plan_for(cfg, n_compute_units, n_tokens, len_after, n_sink=0, window=0):
+    """Host-only.  Returns (status, kvfold_plan_t)."""
+    pl = kvfold_plan_t()
     rc = load_library().kvfold_plan_for(ctypes.byref(cfg) if cfg is not None else None, n_compute_units, n_tokens, len_after,
-                                        ctypes.byref(w), ctypes.byref(s), ctypes.byref(u))
-    return rc, w.value, s.value, u.value
+                                        n_sink, window, ctypes.byref(pl))
+    return rc, pl
 
 
 def kvfold_cache_profile_begin(cache, max_steps) -> int:
@@ -248,14 +259,43 @@ class KvFoldCache:
         import torch
         return torch.cuda.current_stream().cuda_stream
 
-    def step(self, layer, q, k_new, v_new, out, pos_offset=None, lse=None, stream=None, rope=None):
+    def _check(self, name, t, shape, dtype=None):
+        """Marshalling validation: the kernels trust shapes and element types, so a mismatch must stop here."""
+        import torch
+        want = dtype or (torch.float32 if self.dtype_name == "f32" else torch.bfloat16)
+        if not (t.is_cuda and t.device.index == self.cfg.device):
+            raise ValueError(f"{name}: expected a tensor on cuda:{self.cfg.device}, got {t.device}")
+        if t.dtype != want:
+            raise ValueError(f"{name}: expected dtype {want}, got {t.dtype}")
+        if tuple(t.shape) != tuple(shape):
+            raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+        if not t.is_contiguous():
+            raise ValueError(f"{name}: expected a contiguous tensor")
+
+    def step(self, layer, q, k_new, v_new, out, pos_offset=None, lse=None, stream=None, rope=None, window=None):
         """Enqueue one fold step; q/k_new/v_new/out (and lse) are contiguous device tensors.  rope = (cos, sin),
-        fp32 device tensors [n][head_dim/2]: q and k_new are unrotated and the step rotates them."""
-        n = q.shape[0]
+        fp32 device tensors [n][head_dim/2]: q and k_new are unrotated and the step rotates them.  window =
+        (n_sink, window): the sink + sliding-window step."""
+        import torch
+        c = self.cfg
+        n = q.shape[0] if q.dim() == 3 else -1
         pos = self.length(layer) if pos_offset is None else pos_offset
-        for t in (q, k_new, v_new, out):
-            assert t.is_cuda and t.is_contiguous()
+        self._check("q", q, (n, c.n_q_heads, c.head_dim))
+        self._check("out", out, (n, c.n_q_heads, c.head_dim))
+        self._check("k_new", k_new, (n, c.n_kv_heads, c.head_dim))
+        self._check("v_new", v_new, (n, c.n_kv_heads, c.head_dim))
+        if lse is not None:
+            self._check("lse", lse, (c.n_q_heads, n), torch.float32)
         lse_ptr = lse.data_ptr() if lse is not None else None
+        if rope is not None and window is not None:
+            raise ValueError("rope and window are separate entry points")
+        if window is not None:
+            n_sink, win = window
+            rc = kvfold_step_window(self.handle, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), n, pos,
+                                    n_sink, win, out.data_ptr(), lse_ptr, self._stream(stream))
+            if rc:
+                raise KvFoldError(rc, "kvfold_step_window")
+            return out
         if rope is None:
             rc = kvfold_step_ex(self.handle, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), n, pos,
                                 out.data_ptr(), lse_ptr, self._stream(stream))
@@ -263,14 +303,16 @@ class KvFoldCache:
                 raise KvFoldError(rc, "kvfold_step_ex")
             return out
         cos, sin = rope
-        for t in (cos, sin):
-            assert t.is_cuda and t.is_contiguous() and t.dtype.is_floating_point and t.element_size() == 4
-            assert tuple(t.shape) == (n, q.shape[-1] // 2)
+        self._check("rope cos", cos, (n, c.head_dim // 2), torch.float32)
+        self._check("rope sin", sin, (n, c.head_dim // 2), torch.float32)
         rc = kvfold_step_rope(self.handle, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), n, pos,
                               cos.data_ptr(), sin.data_ptr(), out.data_ptr(), lse_ptr, self._stream(stream))
         if rc:
             raise KvFoldError(rc, "kvfold_step_rope")
         return out
+
+    def bytes_required(self) -> int:
+        return kvfold_cache_bytes_required(self.cfg)
 
     def length(self, layer=0) -> int:
         n = kvfold_cache_length(self.handle, layer)

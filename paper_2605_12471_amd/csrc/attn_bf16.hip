@@ -76,7 +76,7 @@ __device__ __forceinline__ float pair_sum(float x) {
 // wait_vm<> + barrier.
 __device__ __forceinline__ void dma16(const unsigned char* base_uniform, unsigned off, unsigned lds_base_uniform) {
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base_uniform), "s"(lds_base_uniform)
-               : "memory");
+               : "memory", "m0");
 }
 // Wait until at most N LDS reads are outstanding (compiler-visible, so that it adds none of its own
 // for fragments covered by this wait).  gfx9 encoding: vmcnt and expcnt left at their maxima.
@@ -221,6 +221,12 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   int my_vis[QB];     // keys visible to this lane's query row
   int vis_first[QB];  // keys visible to the unit's first row (key blocks entirely below need no mask)
   int vis_last0 = 0;  // keys visible to the last row of unit 0: tiles entirely beyond are dead for it
+  // Sink + sliding-window step (Sec. 6 of the paper, the streaming baseline's mask): the row that sees keys
+  // [0, vis) sees of them only j < n_sink and j >= vis - window.  lb_last: the largest such lower bound among
+  // the rows of the wavefront's units; key blocks that begin below it need the left mask.
+  const bool win = p.window > 0;
+  const int n_sink = p.n_sink;
+  int lb_last = 0;
   // pair_units (two-unit kernel): wavefront number n = 4 ug + w of the KV head owns unit n, counted from
   // the first token block, and unit U-1-n, counted from the last, so that every wavefront has the
   // same number of (row, key) pairs to do whatever the causal horizon; else units 2n and 2n+1.
@@ -237,9 +243,11 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     tokc[qb] = tok[qb] < C ? tok[qb] : C - 1;
     unit_valid[qb] = valid;
     store_ok[qb] = valid && (tok[qb] < C);
-    if (qb == 0) {
+    {
       const int last = tb * kRowsPerUnit + kRowsPerUnit - 1;
-      vis_last0 = (int)p.len_prev + (last < C ? last : C - 1) + 1;
+      const int vis_last = (int)p.len_prev + (last < C ? last : C - 1) + 1;
+      if (qb == 0) vis_last0 = vis_last;
+      if (win && vis_last - p.window > lb_last) lb_last = vis_last - p.window;
     }
     my_vis[qb] = (int)p.len_prev + tokc[qb] + 1;
     vis_first[qb] = (int)p.len_prev + tb * kRowsPerUnit + 1;
@@ -257,10 +265,27 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     if (row_hi > C - 1) row_hi = C - 1;
     nkeys_wg = (int)p.len_prev + row_hi + 1;
   }
-  const int ntiles = (nkeys_wg + BN - 1) / BN;
-  const int t_begin = split * p.tiles_per_split;
-  int t_end = t_begin + p.tiles_per_split;
-  if (t_end > ntiles) t_end = ntiles;
+  // logical tiles 0 .. ntiles-1 of this workgroup; under a window the tiles between the sinks and the window
+  // are left out: logical tile t is physical tile t + (t >= ns_t ? skip : 0)
+  TileMap tm;
+  if (win) {
+    const RowRange rr = workgroup_rows(ug, UPW, p.units_per_head, G, C);
+    tm = tile_map(p.len_prev, rr.row_lo, rr.row_hi, n_sink, p.window);
+  } else {
+    tm.ns_t = 0;
+    tm.skip = 0;
+    tm.ntiles = (nkeys_wg + BN - 1) / BN;
+  }
+  const int ns_t = tm.ns_t, t_skip = tm.skip;
+  auto tphys = [&](int t) __attribute__((always_inline)) -> int { return t + (t >= ns_t ? t_skip : 0); };
+  // first logical tile whose physical tile is not below tp
+  auto tlogical = [&](int tp) __attribute__((always_inline)) -> int {
+    if (tp < ns_t) return tp;
+    return tp - t_skip > ns_t ? tp - t_skip : ns_t;
+  };
+  // this workgroup's piece of them, and what its DMA may touch (shared with the host-side model of this walk)
+  const KeyRange kr = key_range(tm, split, p.tiles_per_split, p.len_prev, C, p.k_new != nullptr);
+  const int t_begin = kr.t_begin, t_end = kr.t_end;
 
   const unsigned char* kbase = reinterpret_cast<const unsigned char*>(p.k_cache) + (int64_t)g * p.capacity * ROWB;
   const unsigned char* vbase = reinterpret_cast<const unsigned char*>(p.v_cache) + (int64_t)g * p.capacity * ROWB;
@@ -311,26 +336,22 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   // slab i of tile t of K (is_v = false) or V; CLAMP redirects rows past the cache end, or past this
   // workgroup's key range (the ring runs NV + 1 tiles ahead and knows no end), to the last row inside:
   // they are never used, and so are never fetched from HBM either
-  const unsigned row_lim = (unsigned)(t_end * BN - 1 < Lm1 ? t_end * BN - 1 : Lm1);
-  // Fused append: tiles from t_new on lie in the chunk -- unless this workgroup's key range ends before the
-  // chunk begins: then every row past the range is redirected to row_lim, a cache row, whatever its tile.
-  const bool reaches_chunk = fused && (int64_t)row_lim >= p.len_prev;
-  const int t_new = reaches_chunk ? (int)(p.len_prev / BN) : 0x7fffffff;
-  const unsigned rel_lim = reaches_chunk ? row_lim - (unsigned)p.len_prev : 0u;  // row_lim counted from the chunk's first row
-  auto issue_slab = [&](bool is_v, int t, int slot, int i, auto clamp_tag, unsigned extra = 0) __attribute__((always_inline)) {
+  // (kr.row_lim).  Fused append: tiles from kr.t_new on lie in the chunk -- unless this workgroup's key range ends
+  // before the chunk begins: then every row past the range is redirected to row_lim, a cache row, whatever its tile.
+  const int t_new = kr.t_new;
+  auto issue_slab = [&](bool is_v, int t_log, int slot, int i, auto clamp_tag, unsigned extra = 0) __attribute__((always_inline)) {
     constexpr bool CLAMP = decltype(clamp_tag)::value;
+    const int t = tphys(t_log);
     const unsigned lds = lds0 + (unsigned)(((is_v ? NK : 0) + slot) * TILEB + (w + 4 * i) * 1024);
     unsigned off;
     if (CLAMP) {
       int row0_here = dma_row0;  // opaque copy: what is derived from it is computed here, not once ahead of all
       asm volatile("" : "+v"(row0_here));  // loops and then held in registers through the main loop
       // (wave-uniform choice, scalar selects) a tile of the chunk itself comes from the rows as handed in
-      const bool nw = t >= t_new;
-      const unsigned char* base = nw ? (is_v ? vnew : knew) : (is_v ? vbase : kbase);
-      const unsigned stride = nw ? new_stride : (unsigned)ROWB, lim = nw ? rel_lim : row_lim;
-      unsigned r = (unsigned)((t - (nw ? t_new : 0)) * BN + row0_here + i * 4 * RPS);
-      r = r < lim ? r : lim;
-      off = r * stride + (is_v ? dma_vc : dma_kc) + extra;
+      const DmaRow src = dma_row(kr, t, row0_here + i * 4 * RPS);
+      const unsigned char* base = src.from_chunk ? (is_v ? vnew : knew) : (is_v ? vbase : kbase);
+      const unsigned stride = src.from_chunk ? new_stride : (unsigned)ROWB;
+      off = src.row * stride + (is_v ? dma_vc : dma_kc) + extra;
       dma16(base, off, lds);
     } else {
       off = (is_v ? dma_voff : dma_koff) + (unsigned)(t * BN + i * 4 * RPS) * ROWB;
@@ -460,22 +481,34 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=a"(f) : "v"(kaddr[ks]), "n"(HALFB));
     return f;
   };
-  // causal mask of the 32-key half hh
+  // causal mask (and, under a window, the mask of the keys between the sinks and the window) of the 32-key
+  // half hh (logical numbering)
   auto mask_half = [&](floatx16 (&s)[QB], int hh, int q0 = 0) __attribute__((always_inline)) {
     // (opaque copies: whatever is derived from them is computed here, not once ahead of all loops and
     // then held in registers through the unmasked main loop)
     int hi_here = hi;
     asm volatile("" : "+v"(hi_here));
+    const int key0 = (2 * tphys(hh >> 1) + (hh & 1)) * 32;  // first key of the half
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       if (qb < q0) continue;
-      if (hh * 32 + 32 > vis_first[qb]) {  // wave-uniform
+      if (key0 + 32 > vis_first[qb]) {  // wave-uniform
         int vis_here = my_vis[qb];
         asm volatile("" : "+v"(vis_here));
-        const int rel = vis_here - hh * 32;
+        const int rel = vis_here - key0;
 #pragma unroll
         for (int r = 0; r < 16; ++r)
           if (8 * (r >> 2) + 4 * hi_here + (r & 3) >= rel) s[qb][r] = -INFINITY;
+      }
+      if (win && key0 < lb_last && key0 + 32 > n_sink) {  // wave-uniform
+        int vis_here = my_vis[qb];
+        asm volatile("" : "+v"(vis_here));
+        const int rel_lb = vis_here - p.window - key0, rel_sink = n_sink - key0;  // visible: below rel_sink or from rel_lb on
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kk = 8 * (r >> 2) + 4 * hi_here + (r & 3);
+          if (kk < rel_lb && kk >= rel_sink) s[qb][r] = -INFINITY;
+        }
       }
     }
   };
@@ -810,19 +843,26 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       reset_state();
       // Tiles whose two steps only produce halves entirely below the nearest causal horizon take the
       // fast variant: step 2t+1 produces half 2t+2 = keys [64t+64, 64t+96), so it needs 64t+96 <= vis_min.
-      int t_fast = (vis_min - 96) / BN + 1;  // first tile that is not fast (vis_min >= 1)
+      // (tile bounds are worked out on physical tiles, i.e. on keys, and then turned into logical tile numbers)
+      int t_fast = tlogical((vis_min - 96) / BN + 1);  // first tile that is not fast (vis_min >= 1)
       if (vis_min < 96 || exact) t_fast = 0;
       if (t_fast > t_end) t_fast = t_end;
-      // ... and tiles whose refill (tile t + 1 + NV) lies entirely inside the cache and the key range need no row clamp
-      int t_nc = (Lm1 + 1) / BN - NV - 1;
+      // ... and tiles whose refill (tile t + 1 + NV) lies entirely inside the cache and the key range need no row
+      // clamp (inside the cache proper when the append is fused)
+      int t_nc = tlogical((Lm1 + 1) / BN < t_new ? (Lm1 + 1) / BN : t_new) - NV - 1;
       if (t_nc > t_end - NV - 1) t_nc = t_end - NV - 1;
-      if (t_nc > t_new - NV - 1) t_nc = t_new - NV - 1;  // ... and inside the cache proper when the append is fused
       if (t_nc > t_fast) t_nc = t_fast;
+      // Under a window the first tiles (the sinks, and the tiles that begin below the window of the wavefront's
+      // last row) are masked on the left: tiles [t_begin, t_lead) take the masked variant
+      int t_lead = win ? tlogical((lb_last + BN - 1) / BN) : 0;
+      if (win && t_lead < ns_t) t_lead = ns_t;
+      if (t_lead > t_end) t_lead = t_end;
       // Two-unit kernel: from tile t_dead on every key is beyond the last row of unit 0 and only unit 1
       // is worked on, fast up to its own horizon (t_fast1), masked from there.
-      int t_dead = (vis_last0 + BN - 1) / BN;
+      int t_dead = tlogical((vis_last0 + BN - 1) / BN);
+      if (t_dead < t_lead) t_dead = t_lead;
       if (QB == 1 || exact || t_dead > t_end) t_dead = t_end;
-      int t_fast1 = (vis_first[QB - 1] - 96) / BN + 1;
+      int t_fast1 = tlogical((vis_first[QB - 1] - 96) / BN + 1);
       if (vis_first[QB - 1] < 96 || exact) t_fast1 = 0;
       if (t_fast1 < t_dead) t_fast1 = t_dead;
       if (t_fast1 > t_end) t_fast1 = t_end;
@@ -850,7 +890,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
         }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) mfma_settle_v(sA[qb]);
-        if (t_begin * BN + 32 > vis_min) mask_half(sA, 2 * t_begin);
+        if (win || t_begin * BN + 32 > vis_min) mask_half(sA, 2 * t_begin);
         float mx[QB];
         rowmax_all(sA, mx);
         reference_first(mx, sA);
@@ -864,6 +904,10 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
       }
       int t = t_begin;
       constexpr std::integral_constant<int, 0> both{};
+      for (; t < t_lead; ++t) {
+        step(sA, sB, 2 * t, std::false_type{}, std::true_type{}, std::true_type{}, both);
+        step(sB, sA, 2 * t + 1, std::true_type{}, std::true_type{}, std::true_type{}, both, t + 1 == t_dead && t_dead < t_end);
+      }
       for (; t < t_nc; ++t) {
         step(sA, sB, 2 * t, std::false_type{}, std::false_type{}, std::false_type{}, both);
         step(sB, sA, 2 * t + 1, std::true_type{}, std::false_type{}, std::false_type{}, both);
@@ -975,22 +1019,41 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
 }
 
 template <int D, int QB, int NV>
-static hipError_t launch_one(const AttnParams& p, hipStream_t s) {
+static hipError_t prepare_one() {
   constexpr int lds_bytes = (2 * NV + 1) * kTileKeys * D * 2;
   // per device: the attribute belongs to the device's copy of the kernel (idempotent; a benign race at worst
   // sets it twice)
   static bool attr_done[64] = {};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  bool& attr_set = attr_done[dev];
-  if (!attr_set) {
+  if (!attr_done[dev]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, QB, NV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_done[dev] = true;
   }
+  return hipSuccess;
+}
+
+template <int D, int QB, int NV>
+static hipError_t launch_one(const AttnParams& p, hipStream_t s) {
+  constexpr int lds_bytes = (2 * NV + 1) * kTileKeys * D * 2;
+  hipError_t e = prepare_one<D, QB, NV>();  // a no-op after kvfold_cache_create
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_bf16_kernel<D, QB, NV>), dim3(padded_grid(p.n_wgs)), dim3(256), lds_bytes, s, p);
   return hipGetLastError();
+}
+
+hipError_t prepare_attn_bf16(int head_dim) {
+  hipError_t e = hipErrorInvalidValue;
+  if (head_dim == 128) {
+    e = prepare_one<128, 2, kRingTwoUnits>();
+    if (e == hipSuccess) e = prepare_one<128, 1, kRingOneUnit>();
+  } else if (head_dim == 64) {
+    e = prepare_one<64, 2, kRingTwoUnits>();
+    if (e == hipSuccess) e = prepare_one<64, 1, kRingOneUnit>();
+  }
+  return e;
 }
 
 hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, int qb, hipStream_t s) {

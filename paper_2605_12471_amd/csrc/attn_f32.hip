@@ -20,7 +20,7 @@ __device__ __forceinline__ float pair_sum_f(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int D>
+template <int D, bool WIN>  // WIN: the sink + sliding-window step
 __global__ void __launch_bounds__(256, 2) attn_f32_kernel(AttnParams p) {
   constexpr int CH = D / 4;    // 16-byte chunks per row
   constexpr int ROWB = D * 4;  // bytes per row
@@ -49,9 +49,10 @@ __global__ void __launch_bounds__(256, 2) attn_f32_kernel(AttnParams p) {
     ug = (!p.pair_order || idx < half) ? W - 1 - idx : idx - half;
   }
 
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, hi = l >> 5, m = l & 31;
+  const int tid = threadIdx.x, l = tid & 63, hi = l >> 5, m = l & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: what depends on it alone stays in scalar registers
   const int C = p.n_tokens, Hq = p.n_q_heads, G = p.group;
-  const int64_t L = p.len_prev + C;
+  const int L = (int)p.len_prev + C;  // (row counts fit 32 bits: the host limits the capacity to 2^30 rows)
 
   const int u = ug * kUnitsPerWg + w;
   const int uc = u < p.units_per_head ? u : p.units_per_head - 1;
@@ -60,8 +61,16 @@ __global__ void __launch_bounds__(256, 2) attn_f32_kernel(AttnParams p) {
   const int tok = tb * kRowsPerUnit + m;
   const int tokc = tok < C ? tok : C - 1;
   const bool store_ok = (u < p.units_per_head) && (tok < C);
-  const int64_t my_vis = p.len_prev + tokc + 1;
-  const int64_t vis_first = p.len_prev + (int64_t)tb * kRowsPerUnit + 1;
+  const int my_vis = (int)p.len_prev + tokc + 1;
+  const int vis_first = (int)p.len_prev + tb * kRowsPerUnit + 1;
+  // Sink + sliding-window step (Sec. 6 of the paper, the streaming baseline's mask): of the keys [0, vis) a row
+  // sees only j < n_sink and j >= vis - window; lb_last is the largest such lower bound among the unit's rows
+  constexpr bool win = WIN;
+  int lb_last;
+  {
+    const int last = tb * kRowsPerUnit + kRowsPerUnit - 1;
+    lb_last = (int)p.len_prev + (last < C ? last : C - 1) + 1 - p.window;
+  }
 
   // Q: lane (m, hi) keeps q[m][8*s + 4*hi + j], j = 0..3, s = 0..D/8-1 (contraction slot hi of MFMA (s,j))
   float4 qf[D / 8];
@@ -88,15 +97,26 @@ __global__ void __launch_bounds__(256, 2) attn_f32_kernel(AttnParams p) {
     }
   }
 
-  int64_t nkeys_wg;
+  int nkeys_wg;
   {
     int ulast = ug * kUnitsPerWg + kUnitsPerWg - 1;
     if (ulast > p.units_per_head - 1) ulast = p.units_per_head - 1;
     int row_hi = (ulast / G) * kRowsPerUnit + kRowsPerUnit - 1;
     if (row_hi > C - 1) row_hi = C - 1;
-    nkeys_wg = p.len_prev + row_hi + 1;
+    nkeys_wg = (int)p.len_prev + row_hi + 1;
   }
-  const int ntiles = (int)((nkeys_wg + BN - 1) / BN);
+  // logical tiles 0 .. ntiles-1; under a window the tiles between the sinks and the window are left out:
+  // logical tile t is physical tile t + (t >= ns_t ? skip : 0)
+  TileMap tm;
+  if (win) {
+    const RowRange rr = workgroup_rows(ug, kUnitsPerWg, p.units_per_head, G, C);
+    tm = tile_map(p.len_prev, rr.row_lo, rr.row_hi, p.n_sink, p.window);
+  } else {
+    tm.ns_t = 0;
+    tm.skip = 0;
+    tm.ntiles = (nkeys_wg + BN - 1) / BN;
+  }
+  const int ntiles = tm.ntiles;
   const int t_begin = split * p.tiles_per_split;
   int t_end = t_begin + p.tiles_per_split;
   if (t_end > ntiles) t_end = ntiles;
@@ -114,16 +134,17 @@ __global__ void __launch_bounds__(256, 2) attn_f32_kernel(AttnParams p) {
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = p.scale_log2e;
 
-  for (int t = t_begin; t < t_end; ++t) {
+  for (int t_log = t_begin; t_log < t_end; ++t_log) {
+    const int t = t_log + (t_log >= tm.ns_t ? tm.skip : 0);
     __syncthreads();
 #pragma unroll
     for (int it = 0; it < LD_IT; ++it) {
       const int ci = it * 256 + tid;
       const int row = ci / CH, c = ci % CH;
-      int64_t grow = (int64_t)t * BN + row;
+      int grow = t * BN + row;
       if (grow > L - 1) grow = L - 1;
-      const uint4 kv = *reinterpret_cast<const uint4*>(kbase + grow * ROWB + c * 16);
-      const uint4 vv = *reinterpret_cast<const uint4*>(vbase + grow * ROWB + c * 16);
+      const uint4 kv = *reinterpret_cast<const uint4*>(kbase + (int64_t)grow * ROWB + c * 16);
+      const uint4 vv = *reinterpret_cast<const uint4*>(vbase + (int64_t)grow * ROWB + c * 16);
       *reinterpret_cast<uint4*>(sK + row * ROWB + ((c ^ (row & 15)) * 16)) = kv;
       *reinterpret_cast<uint4*>(sV + row * ROWB + ((c ^ (8 * ((row >> 2) & 1))) * 16)) = vv;
     }
@@ -148,14 +169,23 @@ __global__ void __launch_bounds__(256, 2) attn_f32_kernel(AttnParams p) {
     }
 
     // ---- online softmax
-    const int64_t tile_key0 = (int64_t)t * BN;
-    if (tile_key0 + BN > vis_first) {
+    const int tile_key0 = t * BN;
+    const bool left = WIN && tile_key0 < lb_last && tile_key0 + BN > p.n_sink;  // keys between the sinks and the window
+    if (tile_key0 + BN > vis_first || left) {
+      // visible inside the tile: keys below rel, and of those (window step) the ones below rel_sink or from rel_lb
+      // on; all three are counted from the lane's own first key, 4 * hi
+      // (opaque copy of the lane's half: the 32 key offsets below are formed here, not once ahead of the tile loop
+      // and then held in registers through it)
+      int hi_here = hi;
+      asm volatile("" : "+v"(hi_here));
+      const int rel = my_vis - tile_key0 - 4 * hi_here;
+      const int rel_lb = WIN ? rel - p.window : -1, rel_sink = WIN ? p.n_sink - tile_key0 - 4 * hi_here : 0;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int64_t j = tile_key0 + kb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
-          if (j >= my_vis) s[kb][r] = -INFINITY;
+          const int kk = kb * 32 + 8 * (r >> 2) + (r & 3);  // key offset in the tile, less the lane's 4 * hi
+          if (kk >= rel || (WIN && kk < rel_lb && kk >= rel_sink)) s[kb][r] = -INFINITY;
         }
     }
     float mx = s[0][0];
@@ -229,10 +259,15 @@ __global__ void __launch_bounds__(256, 2) attn_f32_kernel(AttnParams p) {
 }
 
 hipError_t launch_attn_f32(const AttnParams& p, int head_dim, hipStream_t s) {
-  if (head_dim == 128)
-    hipLaunchKernelGGL((attn_f32_kernel<128>), dim3(padded_grid(p.n_wgs)), dim3(256), 0, s, p);
+  const dim3 grid(padded_grid(p.n_wgs));
+  if (head_dim == 128 && p.window > 0)
+    hipLaunchKernelGGL((attn_f32_kernel<128, true>), grid, dim3(256), 0, s, p);
+  else if (head_dim == 128)
+    hipLaunchKernelGGL((attn_f32_kernel<128, false>), grid, dim3(256), 0, s, p);
+  else if (head_dim == 64 && p.window > 0)
+    hipLaunchKernelGGL((attn_f32_kernel<64, true>), grid, dim3(256), 0, s, p);
   else if (head_dim == 64)
-    hipLaunchKernelGGL((attn_f32_kernel<64>), dim3(padded_grid(p.n_wgs)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((attn_f32_kernel<64, false>), grid, dim3(256), 0, s, p);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

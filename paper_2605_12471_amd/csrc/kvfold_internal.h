@@ -3,14 +3,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-namespace kvfold {
+#include "kvfold_consts.h"
+#include "kvfold_plan.h"
 
-// Rows of one (query head, 32-token block) pair are the unit of work of one wavefront.
-constexpr int kRowsPerUnit = 32;
-// Wavefronts (units) per workgroup of the attention kernels.
-constexpr int kUnitsPerWg = 4;
-// Keys per K/V tile staged through LDS.
-constexpr int kTileKeys = 64;
+namespace kvfold {
 
 struct AppendParams {
   const void* k_new;  // [C][Hkv][d]
@@ -62,6 +58,11 @@ struct AttnParams {
   // from here, and every workgroup copies its share of the rows into the cache for the steps to come.
   const void* k_new;
   const void* v_new;
+  // Sink + sliding-window step (window > 0; 0: every key up to the row's own position is visible): the row at
+  // absolute position p sees keys j < n_sink and p - window < j <= p.  Tiles between the sink tiles and the
+  // window are skipped (see tile_map()).
+  int32_t n_sink;
+  int32_t window;
 };
 
 struct CombineParams {
@@ -81,13 +82,15 @@ hipError_t launch_append(const AppendParams& p, hipStream_t s);
 // In-place storage round trip bf16 -> intN -> bf16 (n_bits = 4 or 8) of cache rows [len_prev, len_prev + C) of K and V.
 hipError_t launch_storage_roundtrip(const AppendParams& p, int n_bits, hipStream_t s);
 hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, int units_per_wave, hipStream_t s);
+// Sets the LDS size attribute of every bf16 attention kernel variant of this head dimension on the current
+// device (once per device; launches then have nothing left that could fail for a valid configuration).
+hipError_t prepare_attn_bf16(int head_dim);
 hipError_t launch_attn_f32(const AttnParams& p, int head_dim, hipStream_t s);
 hipError_t launch_combine(const CombineParams& p, hipStream_t s);
 
 // Padded grid size and the XCD-aware remap used by the attention kernels: the hardware hands
 // workgroup b to XCD b % 8, so logical ids are dealt out in 8 contiguous ranges, one per XCD,
 // which keeps the workgroups of one KV head on one XCD's L2.
-constexpr int kNumXcd = 8;
 inline int padded_grid(int n_wgs) { return (n_wgs + kNumXcd - 1) / kNumXcd * kNumXcd; }
 // Logical id (KV head major, then split, then workgroup of the head, heaviest first) of hardware block b.
 // A KV head that spans k = 8 / Hkv XCDs has its workgroups dealt to those XCDs in turn, not in k contiguous

@@ -33,13 +33,13 @@ class GpuFold:
                                     chunk_tokens or cfg.chunk, capacity or cfg.total_tokens, cfg.dtype,
                                     device=self.dev.index or 0)
 
-    def step(self, layer, q, k, v, want_lse=False, rope=None):
+    def step(self, layer, q, k, v, want_lse=False, rope=None, window=None):
         q, k, v = (t.to(self.dev).contiguous() for t in (q, k, v))
         out = torch.empty_like(q)
         lse = torch.empty((self.cfg.n_q_heads, q.shape[0]), dtype=torch.float32, device=self.dev) if want_lse else None
         if rope is not None:
             rope = tuple(t.to(self.dev).contiguous() for t in rope)
-        self.cache.step(layer, q, k, v, out, lse=lse, rope=rope)
+        self.cache.step(layer, q, k, v, out, lse=lse, rope=rope, window=window)
         return (out, lse) if want_lse else out
 
     def close(self):
@@ -52,9 +52,12 @@ def make_oracle(oracle_mod, cfg: I.FoldConfig, capacity=None):
                                   store_dtype=store)
 
 
-def oracle_step(ocache, q, k, v, rows=None, want_weights=False):
-    """q/k/v are the torch tensors handed to the GPU (CPU copies); K/V stored bit-exactly, q widened."""
-    return ocache.step(wide(q), bits(k), bits(v), ocache.len, rows=rows, want_weights=want_weights)
+def oracle_step(ocache, q, k, v, rows=None, want_weights=False, window=None):
+    """q/k/v are the torch tensors handed to the GPU (CPU copies); K/V stored bit-exactly, q widened.
+    window = (n_sink, window): the sink + sliding-window step."""
+    n_sink, win = window if window is not None else (0, None)
+    return ocache.step(wide(q), bits(k), bits(v), ocache.len, rows=rows, want_weights=want_weights,
+                       n_sink=n_sink, window=win)
 
 
 def assert_cache_bit_exact(gpu: GpuFold, ocache, layer=0):

@@ -107,6 +107,9 @@ def test_null_handles(lib):
     assert kv.kvfold_step_ex(None, 0, 1, 1, 1, 1, 0, 1, None, 0) == -1
     assert kv.kvfold_step_rope(None, 0, 1, 1, 1, 1, 0, 16, 16, 1, None, 0) == -1
     assert kv.kvfold_step_rope(None, 0, 1, 1, 1, 1, 0, None, None, 1, None, 0) == -1
+    assert kv.kvfold_step_window(None, 0, 16, 16, 16, 1, 0, 4, 1020, 16, None, 0) == -1
+    assert kv.kvfold_step_window(None, 0, 16, 16, 16, 1, 0, -1, 1020, 16, None, 0) == -1
+    assert kv.kvfold_step_window(None, 0, 16, 16, 16, 1, 0, 4, 0, 16, None, 0) == -1
     assert kv.kvfold_cache_set_length(None, 0, 0) == -1
     assert kv.kvfold_cache_truncate(None, 0, 0) == -1
     assert kv.kvfold_cache_set_tuning(None, 0, 0) == -1
@@ -121,9 +124,9 @@ def test_launch_plans_of_the_benchmark_configurations(lib):
     """The host-side planner on a 256-CU part (no GPU needed): the geometry each benchmark workload is timed in."""
     def plan(Hq, Hkv, d, C, L, dtype=kv.KVFOLD_BF16, cap=131072):
         cfg = binding.make_config(1, Hq, Hkv, d, C, cap, dtype)
-        rc, w, s, u = kv.kvfold_plan_for(cfg, 256, C, L)
+        rc, pl = kv.kvfold_plan_for(cfg, 256, C, L)
         assert rc == 0
-        return w, s, u
+        return pl.n_workgroups, pl.n_splits, pl.units_per_wave
     # config 2 (C=2048 to 16K): first step one unit per wavefront, two workgroups per CU; then one round of 256
     assert plan(32, 8, 128, 2048, 2048) == (512, 1, 1)
     for L in (4096, 8192, 16384):
@@ -148,6 +151,64 @@ def test_launch_plans_of_the_benchmark_configurations(lib):
     assert kv.kvfold_plan_for(cfg, 256, 256, 2048)[0] == -1      # beyond the capacity
     assert kv.kvfold_plan_for(cfg, 0, 256, 1024)[0] == -1
     assert kv.kvfold_plan_for(None, 256, 256, 1024)[0] == -1
+    assert kv.kvfold_plan_for(cfg, 256, 256, 1024, n_sink=-1, window=8)[0] == -1
+    assert kv.kvfold_plan_for(cfg, 256, 256, 1024, n_sink=0, window=-1)[0] == -1
+    assert load_raw_plan_for_null_out(cfg) == -1
+
+
+def load_raw_plan_for_null_out(cfg):
+    return kv.load_library().kvfold_plan_for(ctypes.byref(cfg), 256, 256, 1024, 0, 0, None)
+
+
+def test_fused_append_decision_at_its_limits(lib):
+    """The attention kernel appends by itself only when it can address the chunk's rows, [C][Hkv][d], with 32-bit
+    byte offsets (C * Hkv * d * 2 bytes below 2^32), the cache length is a whole number of 64-key tiles and the
+    cache is bf16; everything else goes through the separate append kernel.  Pinned through the host-only planner."""
+    def fused(Hq, Hkv, d, C, L, dtype=kv.KVFOLD_BF16):
+        cfg = binding.make_config(1, Hq, Hkv, d, C, max(L, C), dtype)
+        rc, pl = kv.kvfold_plan_for(cfg, 256, C, L)
+        assert rc == 0
+        return pl.fused_append
+    assert fused(32, 8, 128, 2048, 16384) == 1
+    assert fused(32, 8, 128, 2048, 2048 + 63) == 0              # cache length 63: a tile would straddle cache and chunk
+    assert fused(32, 8, 128, 2048, 2048 + 64) == 1
+    assert fused(4, 1, 64, 128, 512, kv.KVFOLD_F32) == 0
+    # Hkv = 8, d = 128: a chunk row is 2048 bytes, 2^32 bytes are 2,097,152 tokens
+    assert fused(8, 8, 128, 2097151, 2097151) == 1
+    assert fused(8, 8, 128, 2097152, 2097152) == 0
+    assert fused(8, 8, 128, 4000000, 4000000) == 0
+    # Hkv = 64, d = 128: 16 KiB per token, the limit is 262,144 tokens; d = 64: 524,288
+    assert fused(64, 64, 128, 262143, 262143) == 1
+    assert fused(64, 64, 128, 262144, 262144) == 0
+    assert fused(64, 64, 64, 524287, 524287) == 1
+    assert fused(64, 64, 64, 524288, 524288) == 0
+    # a ragged last chunk of a config whose full chunk is too large is fused again
+    cfg = binding.make_config(1, 8, 8, 128, 4000000, 8000000, kv.KVFOLD_BF16)
+    assert kv.kvfold_plan_for(cfg, 256, 4000000, 4000000)[1].fused_append == 0
+    assert kv.kvfold_plan_for(cfg, 256, 1000000, 5000000 - 5000000 % 64 + 1000000 - 1000000 % 64)[1].fused_append == 1
+
+
+def test_create_rejects_more_kv_heads_than_the_append_grid_holds(lib):
+    cfg = binding.make_config(1, 32768, 32768, 64, 1, 64, kv.KVFOLD_BF16)
+    assert kv.kvfold_cache_create(cfg)[0] == -5
+    cfg = binding.make_config(1, 32767, 32767, 64, 1, 64, kv.KVFOLD_BF16)
+    assert kv.kvfold_cache_bytes_required(cfg) > 0
+
+
+def test_window_plans_do_work_proportional_to_the_window(lib):
+    """Sink + sliding-window step (4 sinks + 1020 recent tokens, Sec. 6) against a 128K cache: the tiles a
+    workgroup walks cover the sink tile, the window and its own rows, not the cache."""
+    cfg = binding.make_config(1, 32, 8, 128, 256, 131072, kv.KVFOLD_BF16)
+    rc, pl = kv.kvfold_plan_for(cfg, 256, 256, 131072, n_sink=4, window=1020)
+    assert rc == 0
+    tiles = pl.n_splits * pl.tiles_per_split
+    assert 17 <= tiles <= 20 * pl.n_splits and pl.tiles_per_split <= 20      # 1 sink tile + (1020 + 64 rows) / 64 + edges
+    assert pl.pair_units == 0 and pl.pair_order == 0
+    rc, plain = kv.kvfold_plan_for(cfg, 256, 256, 131072)
+    assert plain.n_splits * plain.tiles_per_split >= 2048
+    # a window wider than the cache: the plain key range
+    rc, wide = kv.kvfold_plan_for(cfg, 256, 256, 131072, n_sink=0, window=1 << 20)
+    assert wide.n_splits * wide.tiles_per_split >= 2048
 
 
 def test_status_strings(lib):

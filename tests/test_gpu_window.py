@@ -1,0 +1,162 @@
+"""GPU parity of the sink + sliding-window step (kvfold_step_window; the mask of the streaming baseline the
+paper compares with, Sec. 6: a few sink tokens + a window of recent tokens, positions preserved) against the
+oracle's window leg, element by element: small shapes with ragged chunks, forced splits, both wavefront shapes
+and both precisions; windows that cover everything (== the plain step); the paper's 4 + 1020 configuration at
+C = 256 against a 128K cache; plain and windowed steps mixed on one cache."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_12471_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import fold_harness
+    return fold_harness
+
+
+def _run_window_case(H, oracle, cfg, chunks, n_sink, window, splits=0, upw=0):
+    gpu = H.GpuFold(cfg, capacity=sum(chunks), chunk_tokens=max(chunks))
+    oc = H.make_oracle(oracle, cfg, capacity=sum(chunks))
+    if splits:
+        gpu.cache.set_tuning(0, splits)
+    if upw:
+        gpu.cache.set_tuning(1, upw)
+    pos, worst = 0, 0.0
+    try:
+        for step, C in enumerate(chunks):
+            q, k, v = I.chunk_qkv(cfg, 0, step, n_tokens=C, token_base=pos)
+            out, lse = gpu.step(0, q, k, v, want_lse=True, window=(n_sink, window))
+            ref, ref_lse = H.oracle_step(oc, q, k, v, window=(n_sink, window))
+            torch.cuda.synchronize()
+            err = np.abs(H.wide(out) - ref).max()
+            worst = max(worst, err)
+            assert err <= H.TOL[cfg.dtype], f"step {step} C={C} pos={pos} sink={n_sink} window={window}: max|out-oracle|={err}"
+            lerr = np.abs(lse.cpu().double().numpy().T - ref_lse).max()
+            assert lerr <= (1e-5 if cfg.dtype == "f32" else 2e-2), f"step {step}: lse err {lerr}"
+            pos += C
+        H.assert_cache_bit_exact(gpu, oc)
+    finally:
+        gpu.close()
+    return worst
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_sink,window", [(4, 100), (0, 64), (4, 1), (1, 33), (70, 50), (0, 300), (4, 1020), (130, 129)])
+def test_window_small_shapes(H, oracle, dtype, n_sink, window):
+    """Chunks of 96 rows with a ragged tail, up to 11 tiles of cache: windows shorter than a tile, than a unit,
+    longer than the cache; sinks inside one tile, across two, none."""
+    cfg = I.FoldConfig("window_small", 50, 1, 8, 2, 128, 96, 0, dtype)
+    _run_window_case(H, oracle, cfg, [96, 96, 50, 96, 96, 33, 96, 96], n_sink, window)
+
+
+@pytest.mark.parametrize("Hq,Hkv,d,upw", [(4, 1, 64, 1), (7, 1, 128, 2), (7, 1, 128, 1), (6, 3, 64, 2), (32, 8, 128, 2), (2, 2, 128, 2)])
+def test_window_head_shapes_and_wave_shapes(H, oracle, Hq, Hkv, d, upw):
+    """Group sizes 1 ... 7 (units of one workgroup spread over one to eight row blocks, so the workgroup's first
+    window tile and the left-masked tiles of its wavefronts differ), both kernels."""
+    cfg = I.FoldConfig("window_heads", 51, 1, Hq, Hkv, d, 256, 0, "bf16")
+    _run_window_case(H, oracle, cfg, [256, 256, 256, 200, 256], 4, 200, upw=upw)
+    _run_window_case(H, oracle, cfg, [256, 256, 256, 200, 256], 3, 40, upw=upw)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("splits", [2, 3, 5])
+def test_window_with_split_key_range(H, oracle, dtype, splits):
+    cfg = I.FoldConfig("window_split", 52, 1, 8, 2, 128, 64, 0, dtype)
+    _run_window_case(H, oracle, cfg, [64] * 12 + [17], 4, 400, splits=splits)
+    _run_window_case(H, oracle, cfg, [64] * 12 + [17], 66, 130, splits=splits)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_window_that_covers_the_cache_equals_the_plain_step(H, oracle, dtype):
+    """window >= cache length hides nothing: outputs equal the plain step's bit for bit (same tiles, same order)."""
+    cfg = I.FoldConfig("window_all", 53, 1, 8, 2, 128, 128, 0, dtype)
+    chunks = [128, 128, 77, 128]
+    plain = H.GpuFold(cfg, capacity=sum(chunks), chunk_tokens=128)
+    wind = H.GpuFold(cfg, capacity=sum(chunks), chunk_tokens=128)
+    try:
+        pos = 0
+        for step, C in enumerate(chunks):
+            q, k, v = I.chunk_qkv(cfg, 0, step, n_tokens=C, token_base=pos)
+            a, la = plain.step(0, q, k, v, want_lse=True)
+            b, lb = wind.step(0, q, k, v, want_lse=True, window=(0, 1 << 20))
+            assert torch.equal(a, b) and torch.equal(la, lb), f"step {step}"
+            pos += C
+    finally:
+        plain.close()
+        wind.close()
+
+
+def test_plain_and_window_steps_share_one_cache(H, oracle):
+    """The windowed step appends exactly like the plain one, so the two can alternate on one cache (the cache stays
+    complete: nothing is evicted)."""
+    cfg = I.FoldConfig("window_mixed", 54, 1, 8, 2, 128, 128, 0, "bf16")
+    gpu = H.GpuFold(cfg, capacity=6 * 128, chunk_tokens=128)
+    oc = H.make_oracle(oracle, cfg, capacity=6 * 128)
+    try:
+        for step in range(6):
+            q, k, v = I.chunk_qkv(cfg, 0, step)
+            win = (4, 150) if step % 2 else None
+            out = gpu.step(0, q, k, v, window=win)
+            ref, _ = H.oracle_step(oc, q, k, v, window=win)
+            assert np.abs(H.wide(out) - ref).max() <= H.TOL["bf16"], f"step {step}"
+        H.assert_cache_bit_exact(gpu, oc)
+    finally:
+        gpu.close()
+
+
+def test_window_4_sinks_1020_recent_at_128k(H, oracle):
+    """The paper's streaming configuration (Sec. 6: 4 sink tokens + 1020 recent tokens, C = 256, T = 128K): steps
+    of 256 rows under the mask at cache lengths up to 128K, the planner's own launch geometry, every row and head
+    against the oracle; the cache rows are the seeded token stream written in place."""
+    L, C = 131072, 256
+    cfg = I.CONFIGS["deep_chain_128k"].with_(name="window_128k", config_id=7, needle=False)
+    gpu = H.GpuFold(cfg, capacity=L, chunk_tokens=C)
+    oc = H.make_oracle(oracle, cfg, capacity=L)
+    try:
+        kd, vd = gpu.cache.view(0)
+        pos = 0
+        for Lp in (L // 2 - C, L - 2 * C, L - C):            # a step in the middle, then the last two of the chain
+            while pos < Lp:                                    # prefix rows up to Lp, written in place
+                n = min(16384, Lp - pos)
+                _, k, v = I.chunk_qkv(cfg, 0, 0, n_tokens=n, token_base=pos)
+                oc.append(H.bits(k), H.bits(v))
+                kd[:, pos:pos + n].copy_(k.to(kd.device).transpose(0, 1))
+                vd[:, pos:pos + n].copy_(v.to(vd.device).transpose(0, 1))
+                pos += n
+            gpu.cache.set_length(0, Lp)
+            q, k, v = I.chunk_qkv(cfg, 0, 0, n_tokens=C, token_base=Lp)
+            out, lse = gpu.step(0, q, k, v, want_lse=True, window=(4, 1020))
+            ref, ref_lse = H.oracle_step(oc, q, k, v, window=(4, 1020))
+            pos += C
+            err = float(np.abs(H.wide(out) - ref).max())
+            assert err <= H.TOL["bf16"], f"L_prev={Lp}: max|out-oracle| = {err}"
+            assert np.abs(lse.cpu().double().numpy().T - ref_lse).max() <= 2e-2
+            print(f"window 4+1020 at L_prev={Lp}: max-abs error {err}")
+        H.assert_cache_bit_exact(gpu, oc)
+    finally:
+        gpu.close()
+
+
+def test_window_argument_errors(H):
+    import paper_2605_12471_amd as kv
+    cfg = I.FoldConfig("window_err", 55, 1, 8, 2, 128, 64, 0, "bf16")
+    gpu = H.GpuFold(cfg, capacity=128, chunk_tokens=64)
+    try:
+        q, k, v = (t.cuda() for t in I.chunk_qkv(cfg, 0, 0))
+        out = torch.empty_like(q)
+        h = gpu.cache.handle
+        args = (q.data_ptr(), k.data_ptr(), v.data_ptr())
+        assert kv.kvfold_step_window(h, 0, *args, 64, 0, -1, 10, out.data_ptr(), None, 0) == -1
+        assert kv.kvfold_step_window(h, 0, *args, 64, 0, 4, 0, out.data_ptr(), None, 0) == -1
+        assert kv.kvfold_step_window(h, 0, *args, 64, 0, 4, (1 << 30) + 1, out.data_ptr(), None, 0) == -1
+        assert kv.kvfold_step_window(h, 0, *args, 64, 7, 4, 10, out.data_ptr(), None, 0) == -3
+        assert gpu.cache.length(0) == 0
+        assert kv.kvfold_step_window(h, 0, *args, 64, 0, 4, 10, out.data_ptr(), None, 0) == 0
+        torch.cuda.synchronize()
+        assert gpu.cache.length(0) == 64
+    finally:
+        gpu.close()
