@@ -44,7 +44,8 @@ enum {
   KVFOLD_ERR_CAPACITY = -4,    /* length + n_tokens > capacity_tokens (cache untouched)      */
   KVFOLD_ERR_UNSUPPORTED = -5, /* head_dim not in {64,128}, Hq % Hkv != 0, unknown dtype ... */
   KVFOLD_ERR_OOM = -6,         /* device allocation failed / caller buffer too small         */
-  KVFOLD_ERR_HIP = -7          /* any other HIP runtime error (see kvfold_last_hip_error)    */
+  KVFOLD_ERR_HIP = -7,         /* any other HIP runtime error (see kvfold_last_hip_error)    */
+  KVFOLD_ERR_SCRATCH = -8      /* kvfold_step_noalloc: the step exceeds the static scratch   */
 };
 
 /*
@@ -163,6 +164,21 @@ int kvfold_step_rope(kvfold_cache_t* cache, int layer, const void* q, const void
 int kvfold_step_window(kvfold_cache_t* cache, int layer, const void* q, const void* k_new, const void* v_new,
                        int32_t n_tokens, int64_t pos_offset, int32_t n_sink, int64_t window, void* out, float* lse,
                        void* stream);
+
+/*
+ * kvfold_step_ex for callers that can neither allocate device memory nor tolerate a library that does: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, layouts,
+ * results and errors as kvfold_step_ex, but the partial results of a split key range go to a fixed array that
+ * is part of the library's code object (65 MiB per GPU, held until the process ends) instead of the cache's
+ * workspace; the call allocates nothing and frees nothing.  Limit: n_tokens * n_q_heads <= 65536 (two pieces of
+ * the step must fit the array's 131072 (row, piece) slots), else KVFOLD_ERR_SCRATCH and nothing is enqueued;
+ * the number of pieces the planner may use is bounded by the same array.  Every call on one GPU shares that
+ * GPU's array: calls whose work overlaps in time on one GPU (different streams, different caches) race on it;
+ * stream-ordered calls are safe, and nothing in the array has to be cleared between calls (every slot a merge
+ * reads was written by the attention kernel just before it).
+ */
+int kvfold_step_noalloc(kvfold_cache_t* cache, int layer, const void* q, const void* k_new, const void* v_new,
+                        int32_t n_tokens, int64_t pos_offset, void* out, float* lse, void* stream);
 
 /*
  * Destroy a cache: synchronises the device, frees library-owned memory (never

@@ -78,6 +78,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvfold_step_rope.restype = ctypes.c_int
     lib.kvfold_step_window.argtypes = [vp, ctypes.c_int, vp, vp, vp, i32, i64, i32, i64, vp, vp, vp]
     lib.kvfold_step_window.restype = ctypes.c_int
+    lib.kvfold_step_noalloc.argtypes = [vp, ctypes.c_int, vp, vp, vp, i32, i64, vp, vp, vp]
+    lib.kvfold_step_noalloc.restype = ctypes.c_int
     lib.kvfold_cache_destroy.argtypes = [vp]
     lib.kvfold_cache_destroy.restype = ctypes.c_int
     lib.kvfold_cache_length.argtypes = [vp, ctypes.c_int]
@@ -148,6 +150,10 @@ def kvfold_step_rope(cache, layer, q, k_new, v_new, n_tokens, pos_offset, rope_c
 def kvfold_step_window(cache, layer, q, k_new, v_new, n_tokens, pos_offset, n_sink, window, out, lse=None, stream=0) -> int:
     return load_library().kvfold_step_window(cache, layer, q, k_new, v_new, n_tokens, pos_offset, n_sink, window,
                                              out, lse, stream)
+
+
+def kvfold_step_noalloc(cache, layer, q, k_new, v_new, n_tokens, pos_offset, out, lse=None, stream=0) -> int:
+    return load_library().kvfold_step_noalloc(cache, layer, q, k_new, v_new, n_tokens, pos_offset, out, lse, stream)
 
 
 def kvfold_cache_destroy(cache) -> int:
@@ -272,10 +278,11 @@ class KvFoldCache:
         if not t.is_contiguous():
             raise ValueError(f"{name}: expected a contiguous tensor")
 
-    def step(self, layer, q, k_new, v_new, out, pos_offset=None, lse=None, stream=None, rope=None, window=None):
+    def step(self, layer, q, k_new, v_new, out, pos_offset=None, lse=None, stream=None, rope=None, window=None,
+             noalloc=False):
         """Enqueue one fold step; q/k_new/v_new/out (and lse) are contiguous device tensors.  rope = (cos, sin),
         fp32 device tensors [n][head_dim/2]: q and k_new are unrotated and the step rotates them.  window =
-        (n_sink, window): the sink + sliding-window step."""
+        (n_sink, window): the sink + sliding-window step.  noalloc: through kvfold_step_noalloc."""
         import torch
         c = self.cfg
         n = q.shape[0] if q.dim() == 3 else -1
@@ -287,8 +294,8 @@ class KvFoldCache:
         if lse is not None:
             self._check("lse", lse, (c.n_q_heads, n), torch.float32)
         lse_ptr = lse.data_ptr() if lse is not None else None
-        if rope is not None and window is not None:
-            raise ValueError("rope and window are separate entry points")
+        if sum(x is not None and x is not False for x in (rope, window, noalloc)) > 1:
+            raise ValueError("rope, window and noalloc are separate entry points")
         if window is not None:
             n_sink, win = window
             rc = kvfold_step_window(self.handle, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), n, pos,
@@ -297,10 +304,11 @@ class KvFoldCache:
                 raise KvFoldError(rc, "kvfold_step_window")
             return out
         if rope is None:
-            rc = kvfold_step_ex(self.handle, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), n, pos,
-                                out.data_ptr(), lse_ptr, self._stream(stream))
+            fn, name = (kvfold_step_noalloc, "kvfold_step_noalloc") if noalloc else (kvfold_step_ex, "kvfold_step_ex")
+            rc = fn(self.handle, layer, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), n, pos,
+                    out.data_ptr(), lse_ptr, self._stream(stream))
             if rc:
-                raise KvFoldError(rc, "kvfold_step_ex")
+                raise KvFoldError(rc, name)
             return out
         cos, sin = rope
         self._check("rope cos", cos, (n, c.head_dim // 2), torch.float32)

@@ -46,7 +46,30 @@ int hip_fail(hipError_t e) {
   return e == hipErrorOutOfMemory ? KVFOLD_ERR_OOM : KVFOLD_ERR_HIP;
 }
 
+// ---- static scratch of kvfold_step_noalloc: split partials for callers that cannot allocate ------------
+// One array per GPU, part of the library's code object, alive until the process ends.  Holds the (max, sum)
+// pairs of kStaticScratchRows (row, split) pairs first, then their unnormalised partial outputs (head_dim
+// floats each, 128 at most).  Host code never uses the symbol itself as an address: the per-device pointer
+// comes from hipGetSymbolAddress, once per device.
+constexpr int64_t kStaticScratchRows = 1 << 17;                                    // (row, split) pairs
+constexpr size_t kStaticScratchBytes = (size_t)kStaticScratchRows * (128 + 2) * sizeof(float);  // 65 MiB
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this device's copy of the scratch array (the device must be current).
+int static_scratch(int device, unsigned char** out) {
+  if (device < 0 || device >= kMaxDevices) return KVFOLD_ERR_INVALID_ARG;
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (!ptr) return KVFOLD_ERR_HIP;
+    g_scratch_ptr[device] = static_cast<unsigned char*>(ptr);
+  }
+  *out = g_scratch_ptr[device];
+  return KVFOLD_OK;
+}
 
 struct DeviceGuard {
   int prev = -1;
@@ -101,6 +124,8 @@ int kvfold_cache_create(const kvfold_config_t* cfg, kvfold_cache_t** out_cache) 
   // whatever a launch could still refuse (the attention kernels' LDS size) is settled here, so that a step
   // never fails with part of its work already on the stream
   if (e == hipSuccess && cfg->dtype == KVFOLD_BF16) e = prepare_attn_bf16(cfg->head_dim);
+  unsigned char* scratch_ptr = nullptr;
+  if (e == hipSuccess && static_scratch(cfg->device, &scratch_ptr) != KVFOLD_OK) e = hipErrorInvalidSymbol;
   if (e != hipSuccess) {
     delete c;
     return hip_fail(e);
@@ -148,6 +173,7 @@ struct StepOpts {
   const float* rope_sin = nullptr;
   int32_t n_sink = 0;               // sink + sliding-window step when window > 0
   int64_t window = 0;
+  bool static_scratch = false;      // split partials go to the library's static array instead of the cache's workspace
 };
 
 // One fold step.
@@ -171,6 +197,16 @@ int step_impl(kvfold_cache_t* c, int layer, const void* q, const void* k_new, co
   // where the split partials go, and how many (row, split) pairs fit there
   PlanCtx pc = c->pc;
   float *part_o = c->ws_o, *part_ml = c->ws_ml;
+  if (opt.static_scratch) {
+    unsigned char* sp = nullptr;
+    const int rc = static_scratch(f.device, &sp);
+    if (rc != KVFOLD_OK) return rc;
+    const int64_t rows = (int64_t)n_tokens * f.n_q_heads;
+    if (2 * rows > kStaticScratchRows) return KVFOLD_ERR_SCRATCH;  // not even two pieces of this step fit
+    pc.ws_rows = kStaticScratchRows;
+    part_ml = reinterpret_cast<float*>(sp);
+    part_o = reinterpret_cast<float*>(sp + (size_t)kStaticScratchRows * 2 * sizeof(float));
+  }
 
   const size_t layer_block = (size_t)f.n_kv_heads * (size_t)f.capacity_tokens * (size_t)f.head_dim * c->elem_bytes;
   unsigned char* k_layer = c->kv + (size_t)layer * layer_block;
@@ -297,6 +333,13 @@ int kvfold_step_window(kvfold_cache_t* c, int layer, const void* q, const void* 
   StepOpts opt;
   opt.n_sink = n_sink;
   opt.window = window;
+  return step_impl(c, layer, q, k_new, v_new, n_tokens, pos_offset, opt, out, lse, stream);
+}
+
+int kvfold_step_noalloc(kvfold_cache_t* c, int layer, const void* q, const void* k_new, const void* v_new,
+                        int32_t n_tokens, int64_t pos_offset, void* out, float* lse, void* stream) {
+  StepOpts opt;
+  opt.static_scratch = true;
   return step_impl(c, layer, q, k_new, v_new, n_tokens, pos_offset, opt, out, lse, stream);
 }
 

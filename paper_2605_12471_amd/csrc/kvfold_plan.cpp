@@ -219,6 +219,7 @@ const char* kvfold_status_string(int status) {
     case KVFOLD_ERR_UNSUPPORTED: return "unsupported configuration";
     case KVFOLD_ERR_OOM: return "out of device memory or buffer too small";
     case KVFOLD_ERR_HIP: return "HIP runtime error";
+    case KVFOLD_ERR_SCRATCH: return "step does not fit the static scratch buffer";
     default: return "unknown status";
   }
 }

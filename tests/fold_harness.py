@@ -33,13 +33,13 @@ class GpuFold:
                                     chunk_tokens or cfg.chunk, capacity or cfg.total_tokens, cfg.dtype,
                                     device=self.dev.index or 0)
 
-    def step(self, layer, q, k, v, want_lse=False, rope=None, window=None):
+    def step(self, layer, q, k, v, want_lse=False, rope=None, window=None, noalloc=False):
         q, k, v = (t.to(self.dev).contiguous() for t in (q, k, v))
         out = torch.empty_like(q)
         lse = torch.empty((self.cfg.n_q_heads, q.shape[0]), dtype=torch.float32, device=self.dev) if want_lse else None
         if rope is not None:
             rope = tuple(t.to(self.dev).contiguous() for t in rope)
-        self.cache.step(layer, q, k, v, out, lse=lse, rope=rope, window=window)
+        self.cache.step(layer, q, k, v, out, lse=lse, rope=rope, window=window, noalloc=noalloc)
         return (out, lse) if want_lse else out
 
     def close(self):

@@ -110,6 +110,7 @@ def test_null_handles(lib):
     assert kv.kvfold_step_window(None, 0, 16, 16, 16, 1, 0, 4, 1020, 16, None, 0) == -1
     assert kv.kvfold_step_window(None, 0, 16, 16, 16, 1, 0, -1, 1020, 16, None, 0) == -1
     assert kv.kvfold_step_window(None, 0, 16, 16, 16, 1, 0, 4, 0, 16, None, 0) == -1
+    assert kv.kvfold_step_noalloc(None, 0, 16, 16, 16, 1, 0, 16, None, 0) == -1
     assert kv.kvfold_cache_set_length(None, 0, 0) == -1
     assert kv.kvfold_cache_truncate(None, 0, 0) == -1
     assert kv.kvfold_cache_set_tuning(None, 0, 0) == -1
@@ -212,8 +213,8 @@ def test_window_plans_do_work_proportional_to_the_window(lib):
 
 
 def test_status_strings(lib):
-    seen = {kv.kvfold_status_string(s) for s in range(0, -8, -1)}
-    assert len(seen) == 8 and "unknown status" not in seen
+    seen = {kv.kvfold_status_string(s) for s in range(0, -9, -1)}
+    assert len(seen) == 9 and "unknown status" not in seen
     assert kv.kvfold_status_string(-99) == "unknown status"
 
 
