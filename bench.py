@@ -37,7 +37,7 @@ PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA (256 CU x 4096 FLOP/clk x 2
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-KERNEL_SOURCES = ("attn_bf16.hip", "kvfold_internal.h")
+KERNEL_SOURCES = ("attn_bf16.hip", "kvfold_internal.h", "kvfold_consts.h")
 
 
 def kernel_source_hash():
@@ -348,6 +348,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="full_stack_128k")
     ap.add_argument("--layers", type=int, default=0, help="override the workload's number of layers (0 = as defined)")
+    ap.add_argument("--chunk", type=int, default=0, help="override the workload's chunk length (0 = as defined)")
+    ap.add_argument("--dtype", default="", choices=["", "bf16", "f32"], help="override the workload's element type")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=160, help="sample rows of the oracle's timed leg")
@@ -356,6 +358,8 @@ def main():
     ap.add_argument("--units-per-wave", type=int, default=0)
     ap.add_argument("--decode-shaped-only", action="store_true",
                     help="run only the decode-shaped points (1..16 tokens against a 128K cache) and print them: for profiling")
+    ap.add_argument("--window-only", action="store_true",
+                    help="run only the sink + sliding-window steps (4 + 1020 at C = 256 against 128K) and print them: for profiling")
     ap.add_argument("--separate-append", action="store_true",
                     help="run the append as its own kernel (a plain copy of known size: the calibration of the HBM counters)")
     args = ap.parse_args()
@@ -377,9 +381,16 @@ def main():
     if args.decode_shaped_only:
         print(json.dumps({"decode_shaped_128k": decode_shaped_points(torch, kv, I, dev)}))
         return
+    if args.window_only:
+        print(json.dumps({"window_4_1020_C256_128k": window_steps(torch, kv, I, dev)}))
+        return
     cfg = I.CONFIGS[args.workload]
     if args.layers:
         cfg = cfg.with_(n_layers=args.layers)
+    if args.chunk:
+        cfg = cfg.with_(chunk=args.chunk)
+    if args.dtype:
+        cfg = cfg.with_(dtype=args.dtype)
     tuning = {}
     if args.splits:
         tuning[kv.TUNE_SPLITS] = args.splits

@@ -242,9 +242,8 @@ int kvfold_cache_set_storage_roundtrip(kvfold_cache_t* cache, int32_t n_bits);
  *                              block of the chunk (evens out the causal part); 0 = automatic (single
  *                              round of workgroups), 1 = never, 2 = always.
  *   KVFOLD_TUNE_FUSED_APPEND   bf16 mode: the attention kernel copies the chunk's rows into the cache itself
- *                              (and reads the chunk's own tiles from k_new / v_new) whenever the cache
- *                              length is a multiple of 64, neither rotary embedding nor a storage
- *                              round trip is in play, and n_tokens * n_kv_heads * head_dim * 2 bytes is
+ *                              (and reads the chunk's own rows from k_new / v_new) whenever neither rotary
+ *                              embedding nor a storage round trip is in play and n_tokens * n_kv_heads * head_dim * 2 bytes is
  *                              below 2^32 (the kernel addresses the chunk with 32-bit byte offsets; larger
  *                              chunks go through the separate append kernel); 0 = automatic, 1 = never.
  *                              Either way k_new / v_new must stay valid until the step's work on the

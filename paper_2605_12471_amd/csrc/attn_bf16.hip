@@ -338,7 +338,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
   // they are never used, and so are never fetched from HBM either
   // (kr.row_lim).  Fused append: tiles from kr.t_new on lie in the chunk -- unless this workgroup's key range ends
   // before the chunk begins: then every row past the range is redirected to row_lim, a cache row, whatever its tile.
-  const int t_new = kr.t_new;
+  const int t_new = kr.t_straddle >= 0 ? kr.t_straddle : kr.t_new;  // first physical tile with rows of the chunk
   auto issue_slab = [&](bool is_v, int t_log, int slot, int i, auto clamp_tag, unsigned extra = 0) __attribute__((always_inline)) {
     constexpr bool CLAMP = decltype(clamp_tag)::value;
     const int t = tphys(t_log);
@@ -347,12 +347,21 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     if (CLAMP) {
       int row0_here = dma_row0;  // opaque copy: what is derived from it is computed here, not once ahead of all
       asm volatile("" : "+v"(row0_here));  // loops and then held in registers through the main loop
-      // (wave-uniform choice, scalar selects) a tile of the chunk itself comes from the rows as handed in
       const DmaRow src = dma_row(kr, t, row0_here + i * 4 * RPS);
-      const unsigned char* base = src.from_chunk ? (is_v ? vnew : knew) : (is_v ? vbase : kbase);
-      const unsigned stride = src.from_chunk ? new_stride : (unsigned)ROWB;
-      off = src.row * stride + (is_v ? dma_vc : dma_kc) + extra;
-      dma16(base, off, lds);
+      if (__builtin_expect(t != kr.t_straddle, 1)) {
+        // (wave-uniform choice, scalar selects) a tile of the chunk itself comes from the rows as handed in
+        const bool nw = t >= kr.t_new;
+        const unsigned char* base = nw ? (is_v ? vnew : knew) : (is_v ? vbase : kbase);
+        const unsigned stride = nw ? new_stride : (unsigned)ROWB;
+        off = src.row * stride + (is_v ? dma_vc : dma_kc) + extra;
+        dma16(base, off, lds);
+      } else if (src.from_chunk) {
+        // the one tile with rows on both sides of the cache's end (cache length not a multiple of the tile): each
+        // lane fetches from its own side, two DMA instructions with complementary lanes fill the slab
+        dma16(is_v ? vnew : knew, src.row * new_stride + (is_v ? dma_vc : dma_kc) + extra, lds);
+      } else {
+        dma16(is_v ? vbase : kbase, src.row * (unsigned)ROWB + (is_v ? dma_vc : dma_kc) + extra, lds);
+      }
     } else {
       off = (is_v ? dma_voff : dma_koff) + (unsigned)(t * BN + i * 4 * RPS) * ROWB;
       dma16(is_v ? vbase : kbase, off, lds);

@@ -70,14 +70,16 @@ KVFOLD_HD TileMap tile_map(long long len_prev, int row_lo, int row_hi, int n_sin
 // Piece `split` of a workgroup's logical tiles, [t_begin, t_end), and what the DMA of its K/V tiles may touch.
 // The LDS ring runs a few tiles ahead and knows no end, so every source row is clamped to row_lim, the last row
 // of the piece that exists (the cache holds rows [0, len_prev + n_tokens)).  With the append fused into the
-// attention kernel the chunk's rows are not in the cache yet: physical tiles from t_new on are read from the
-// rows as handed in, [n_tokens][Hkv][d], relative to the chunk's first row and clamped to rel_lim -- unless the
-// piece ends before the chunk begins, in which case nothing is ever read from there.
+// attention kernel the chunk's rows are not in the cache yet: rows from chunk_row0 = len_prev on are read from the
+// rows as handed in, [n_tokens][Hkv][d], counted from the chunk's first row -- unless the piece ends before the
+// chunk begins, in which case nothing is ever read from there.  Physical tiles from t_new on lie wholly in the
+// chunk; when len_prev is not a multiple of the tile, tile t_straddle = t_new - 1 holds rows of both.
 struct KeyRange {
-  int t_begin, t_end;  // logical tiles
-  unsigned row_lim;    // last cache row a DMA of this piece may read
-  int t_new;           // first physical tile read from the chunk as handed in (INT_MAX: none)
-  unsigned rel_lim;    // last chunk row (counted from the chunk's first) a DMA of this piece may read
+  int t_begin, t_end;   // logical tiles
+  unsigned row_lim;     // last row (cache numbering) a DMA of this piece may read
+  unsigned chunk_row0;  // first row that comes from the chunk as handed in (0xffffffff: none does)
+  int t_new;            // first physical tile that lies wholly in the chunk (INT_MAX: none)
+  int t_straddle;       // physical tile with rows on both sides of chunk_row0 (-1: none)
 };
 KVFOLD_HD KeyRange key_range(const TileMap& tm, int split, int tiles_per_split, long long len_prev, int n_tokens, bool fused) {
   KeyRange k;
@@ -90,8 +92,9 @@ KVFOLD_HD KeyRange key_range(const TileMap& tm, int split, int tiles_per_split, 
   const long long lim = row_end < Lm1 ? row_end : Lm1;
   k.row_lim = (unsigned)(lim < 0 ? 0 : lim);
   const bool reaches_chunk = fused && lim >= len_prev;
-  k.t_new = reaches_chunk ? (int)(len_prev / kTileKeys) : 0x7fffffff;
-  k.rel_lim = reaches_chunk ? (unsigned)(lim - len_prev) : 0u;
+  k.chunk_row0 = reaches_chunk ? (unsigned)len_prev : 0xffffffffu;
+  k.t_new = reaches_chunk ? (int)((len_prev + kTileKeys - 1) / kTileKeys) : 0x7fffffff;
+  k.t_straddle = reaches_chunk && len_prev % kTileKeys ? (int)(len_prev / kTileKeys) : -1;
   return k;
 }
 
@@ -102,11 +105,11 @@ struct DmaRow {
   unsigned row;
 };
 KVFOLD_HD DmaRow dma_row(const KeyRange& k, int t_phys, int row_in_tile) {
+  unsigned r = (unsigned)(t_phys * kTileKeys + row_in_tile);
+  r = r < k.row_lim ? r : k.row_lim;
   DmaRow d;
-  d.from_chunk = t_phys >= k.t_new;
-  const unsigned r = (unsigned)((t_phys - (d.from_chunk ? k.t_new : 0)) * kTileKeys + row_in_tile);
-  const unsigned lim = d.from_chunk ? k.rel_lim : k.row_lim;
-  d.row = r < lim ? r : lim;
+  d.from_chunk = r >= k.chunk_row0;
+  d.row = d.from_chunk ? r - k.chunk_row0 : r;
   return d;
 }
 

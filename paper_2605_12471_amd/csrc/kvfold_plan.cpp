@@ -48,7 +48,7 @@ int64_t workspace_rows(const kvfold_config_t* cfg) {
 bool fused_append_applies(const PlanCtx& c, int n_tokens, int64_t len_prev, bool rope) {
   const kvfold_config_t& f = c.cfg;
   if (f.dtype != KVFOLD_BF16 || rope || c.storage_bits || c.tune_fused_append == 1) return false;
-  if (len_prev % kTileKeys != 0) return false;
+  (void)len_prev;  // any cache length: a tile that straddles the cache's end is filled from both sides
   const int64_t chunk_bytes = (int64_t)n_tokens * f.n_kv_heads * f.head_dim * elem_size(f.dtype);
   return chunk_bytes < ((int64_t)1 << 32);
 }

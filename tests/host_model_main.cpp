@@ -85,7 +85,8 @@ static void walk_step(const kvfold_config_t& cfg, int n_cu, int n_tokens, int64_
     for (int split = 0; split < pl.n_splits; ++split) {
       const KeyRange kr = key_range(tm, split, pl.tiles_per_split, len_prev, n_tokens, fused);
       if (kr.t_begin >= kr.t_end) continue;  // an empty piece touches nothing
-      const int64_t readable_cache = fused ? (kr.t_new == 0x7fffffff ? len_after : len_prev) : len_after;
+      // (a piece that never reads the chunk as handed in ends below len_prev, so the clamp keeps it there too)
+      const int64_t readable_cache = fused ? len_prev : len_after;
       REQUIRE((int64_t)kr.row_lim < len_after, "row_lim");
       for (int t = kr.t_begin; t < kr.t_end + kRunAhead; ++t) {
         const int tp = t + (t >= tm.ns_t ? tm.skip : 0);

@@ -163,16 +163,16 @@ def load_raw_plan_for_null_out(cfg):
 
 def test_fused_append_decision_at_its_limits(lib):
     """The attention kernel appends by itself only when it can address the chunk's rows, [C][Hkv][d], with 32-bit
-    byte offsets (C * Hkv * d * 2 bytes below 2^32), the cache length is a whole number of 64-key tiles and the
-    cache is bf16; everything else goes through the separate append kernel.  Pinned through the host-only planner."""
+    byte offsets (C * Hkv * d * 2 bytes below 2^32) and the cache is bf16; everything else goes through the
+    separate append kernel.  Pinned through the host-only planner."""
     def fused(Hq, Hkv, d, C, L, dtype=kv.KVFOLD_BF16):
         cfg = binding.make_config(1, Hq, Hkv, d, C, max(L, C), dtype)
         rc, pl = kv.kvfold_plan_for(cfg, 256, C, L)
         assert rc == 0
         return pl.fused_append
     assert fused(32, 8, 128, 2048, 16384) == 1
-    assert fused(32, 8, 128, 2048, 2048 + 63) == 0              # cache length 63: a tile would straddle cache and chunk
-    assert fused(32, 8, 128, 2048, 2048 + 64) == 1
+    assert fused(32, 8, 128, 2048, 2048 + 63) == 1              # any cache length: a straddling tile is filled from both sides
+    assert fused(32, 8, 128, 1, 131072) == 1                    # decode-shaped steps: two launches (attention, merge)
     assert fused(4, 1, 64, 128, 512, kv.KVFOLD_F32) == 0
     # Hkv = 8, d = 128: a chunk row is 2048 bytes, 2^32 bytes are 2,097,152 tokens
     assert fused(8, 8, 128, 2097151, 2097151) == 1

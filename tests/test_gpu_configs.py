@@ -93,11 +93,14 @@ def test_config3_deep_chain_needle_128k(H, oracle):
 
 
 def test_config4_full_stack_32_layers_128k(H, oracle):
-    """32 independent layers, C=4096, 32 steps each, 16 GiB of K/V resident; three layers checked."""
+    """32 independent layers, C=4096, 32 steps each, 16 GiB of K/V resident; three layers checked, the others
+    run alongside (cross-layer isolation: a layer's output and cache must not depend on its neighbours')."""
     cfg = I.CONFIGS["full_stack_128k"]
     free, _ = torch.cuda.mem_get_info()
     assert free > 24 * 2 ** 30, "needs the 16 GiB cache plus staging"
-    worst, _, _ = _run_sampled(H, oracle, cfg, [0, 13, 31], steps=[0, 1, 16, 31], rows_random=8)
+    # sample of the measurement plan: steps {0, 1, 2, 16, 30, 31} + 8 seeded ones, rows {0, 1, C/2, C-2, C-1} + 16
+    # seeded ones per step, all 32 heads, on layers 0, 13 and 31
+    worst, _, _ = _run_sampled(H, oracle, cfg, [0, 13, 31])
     print("config 4 worst max-abs error", worst)
 
 

@@ -138,3 +138,58 @@ def test_rope_step_at_the_size_of_the_llama_layer(H, oracle):
         print(f"\nrope at config-2 size: worst max-abs error {worst:.2e}")
     finally:
         gpu.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rope_step_against_an_fp64_complex_rotation(H, oracle, dtype):
+    """An fp64 leg that shares nothing with the fp32 rounding points chosen for the step: every (x_j, x_{j+d/2}) pair
+    is rotated as a complex number in double precision, z' = z * (cos + i sin).  The keys the step leaves in the cache
+    must lie within the rounding budget of that exact rotation (half a unit in the last place of the mode dtype plus
+    the fp32 arithmetic error, which is relative to the operands), and the outputs
+    must match the fold of the fp64-rotated inputs (keys rounded once to the mode dtype, queries unrounded)."""
+    d, Hq, Hkv = 128, 8, 2
+    chunks = [160, 96, 50]
+    cfg = I.FoldConfig("rope64", 17, 1, Hq, Hkv, d, max(chunks), 0, dtype)
+    cap = sum(chunks)
+    gpu = H.GpuFold(cfg, capacity=cap, chunk_tokens=max(chunks))
+    oc = H.make_oracle(oracle, cfg, capacity=cap)
+    mant = 8 if dtype == "bf16" else 24          # significand bits of the mode dtype
+
+    def rotate64(x, cos, sin):
+        z = x[..., : d // 2].astype(np.float64) + 1j * x[..., d // 2:].astype(np.float64)
+        z = z * (cos.astype(np.float64) + 1j * sin.astype(np.float64))[:, None, :]
+        return np.concatenate([z.real, z.imag], axis=-1)
+
+    pos = 0
+    try:
+        for step, C in enumerate(chunks):
+            q, k, v = I.chunk_qkv(cfg, 0, step, n_tokens=C, token_base=pos)
+            cos, sin = I.rope_tables(d, pos, C)
+            out = gpu.step(0, q, k, v, rope=(cos, sin))
+            k64 = rotate64(H.wide(k), cos.numpy(), sin.numpy())                 # [C][Hkv][d], exact up to fp64 rounding
+            q64 = rotate64(H.wide(q), cos.numpy(), sin.numpy())
+            Kc, _ = gpu.cache.view(0)
+            torch.cuda.synchronize()
+            got = H.wide(Kc[:, pos:pos + C].transpose(0, 1))                    # [C][Hkv][d]
+            # Error budget of the stored key against the exact rotation: the final rounding to the mode dtype (half a
+            # unit in the last place) plus the step's fp32 arithmetic before it -- the sine product and the fused
+            # multiply-add each round once, relative to the operands (not to the result, which may cancel):
+            # at most 2^-22 (|x_j| + |x_{j+d/2}|).
+            kw = H.wide(k)
+            mag = np.abs(kw[..., : d // 2]) + np.abs(kw[..., d // 2:])
+            mag = np.concatenate([mag, mag], axis=-1)
+            big = np.maximum(np.maximum(np.abs(k64), np.abs(got)), 1e-30)
+            ulp = np.exp2(np.floor(np.log2(big)) - (mant - 1))
+            assert np.all(np.abs(got - k64) <= 0.5 * ulp + 2.0 ** -22 * mag), \
+                f"step {step}: stored key off the fp64 rotation by more than its rounding budget"
+            # outputs: the oracle's fold on the fp64-rotated inputs, keys rounded once (RNE) to the mode dtype
+            if dtype == "bf16":
+                k_store = oracle.f32_to_bf16_bits(k64.astype(np.float32))
+            else:
+                k_store = k64.astype(np.float32)
+            ref, _ = oc.step(q64, k_store, H.bits(v), oc.len)
+            err = np.abs(H.wide(out) - ref).max()
+            assert err <= H.TOL[dtype], f"step {step}: max|out - fp64-rotated fold| = {err}"
+            pos += C
+    finally:
+        gpu.close()
