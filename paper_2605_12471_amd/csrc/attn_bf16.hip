@@ -322,7 +322,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
 #pragma unroll
     for (int u = 0; u < kCopyFirst; ++u)
       if (tid + u * 256 < 2 * copy_nvec) copy_v[u] = *copy_src(tid + u * 256);
-    for (int idx = tid + kCopyFirst * 256; idx < 2 * copy_nvec; idx += 256) *copy_dst(idx) = *copy_src(idx);
+    for (int idx = tid + kCopyFirst * 256; idx < 2 * copy_nvec; idx += 256) __builtin_nontemporal_store(*copy_src(idx), copy_dst(idx));
   }
 
   // ---- DMA addressing: wavefront w moves slabs w, w+4, ...; lane l lands at chunk (l % CH) of row
@@ -403,7 +403,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
     if (fused) {
 #pragma unroll
       for (int u = 0; u < kCopyFirst; ++u)
-        if (tid + u * 256 < 2 * copy_nvec) *copy_dst(tid + u * 256) = copy_v[u];
+        if (tid + u * 256 < 2 * copy_nvec) __builtin_nontemporal_store(copy_v[u], copy_dst(tid + u * 256));
     }
     if (p.rope_cos) {
       // Rotary embedding at the row's absolute position (Sec. 2), half-split pairs (j, j + D/2), fp32 with
@@ -998,7 +998,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
         const int r = i * RPI + l / CPR, c = l % CPR;
         const uintx4 x = *LDS_PTR(const uintx4, obase + (unsigned)(r * OROWH + c * 16));
         if (unit_valid[qb] && tok0 + r < C)
-          *reinterpret_cast<uintx4*>(reinterpret_cast<__bf16*>(p.out) + ((int64_t)(tok0 + r) * Hq + head[qb]) * D + c * 8) = x;
+          __builtin_nontemporal_store(x, reinterpret_cast<uintx4*>(reinterpret_cast<__bf16*>(p.out) + ((int64_t)(tok0 + r) * Hq + head[qb]) * D + c * 8));
       }
     } else {
 #pragma unroll
@@ -1021,7 +1021,7 @@ __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1)) attn_bf16_kernel(AttnP
         const int r = i * RPI + l / CPR, c = l % CPR;
         const floatx4 x = *LDS_PTR(const floatx4, obase + (unsigned)(r * OROWF + c * 16));
         if (unit_valid[qb] && tok0 + r < C)
-          *reinterpret_cast<floatx4*>(p.part_o + ((int64_t)split * n_rows + (int64_t)(tok0 + r) * Hq + head[qb]) * D + c * 4) = x;
+          __builtin_nontemporal_store(x, reinterpret_cast<floatx4*>(p.part_o + ((int64_t)split * n_rows + (int64_t)(tok0 + r) * Hq + head[qb]) * D + c * 4));
       }
     }
   }

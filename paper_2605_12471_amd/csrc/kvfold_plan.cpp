@@ -87,6 +87,7 @@ Plan plan_with(const PlanCtx& c, int n_tokens, int64_t len_after, int upw, int n
   if (s_max > kMaxSplits) s_max = kMaxSplits;
   if (s_max < 1) s_max = 1;
   int64_t s = 1;
+  pl.est_seconds = 0.0;
   if (c.tune_splits > 0) {
     s = c.tune_splits;
   } else {
@@ -99,8 +100,14 @@ Plan plan_with(const PlanCtx& c, int n_tokens, int64_t len_after, int upw, int n
     //    the length of the lightest workgroups only (first token block: the prefix and little else).
     //  * A residue of imbalance that more rounds even out, 8 us of start and end per round of workgroups,
     //    and for s > 1 the fp32 partials written and read once at 4 TB/s plus the combine launch.
-    const int64_t slots = (int64_t)c.n_cu * (upw == 1 ? 2 : 1);
-    const double flops = 4.0 * f.n_q_heads * f.head_dim * pairs;
+    //  * Matrix work counts the padding of the last workgroup of a KV head (units that do not exist are computed
+    //    all the same), and 10 % more in the one-unit kernel, where every LDS fragment feeds one MFMA instead of two.
+    //    A one-unit grid of at most one workgroup per CU runs one wavefront per SIMD with nothing to overlap with:
+    //    7 % less than two per CU deliver between them (measured on the C = 128, G = 7 fold: 8 pieces on 224 CUs
+    //    beat 18 pieces on all 256 twice over by 3 %).
+    const double pad = (double)((int64_t)pl.wgs_per_head * per_wg) / (double)pl.units_per_head;
+    const double kernel_cost = upw == 2 ? 1.0 : 1.1;
+    const double flops = 4.0 * f.n_q_heads * f.head_dim * pairs * pad * kernel_cost;
     const double kv_rows = window > 0 ? std::min((double)len_after, (double)ntiles * kTileKeys * pl.wgs_per_head) : (double)len_after;
     const double kv_bytes = 2.0 * f.n_kv_heads * f.head_dim * (double)elem_size(f.dtype) * kv_rows;
     const double t_attn = std::max(flops / (f.dtype == KVFOLD_BF16 ? 1.35e15 : 1.2e14), kv_bytes / 5e12);  // bf16 / fp32 MFMA rates
@@ -111,13 +118,16 @@ Plan plan_with(const PlanCtx& c, int n_tokens, int64_t len_after, int upw, int n
       const int64_t tps = (ntiles + cand - 1) / cand;
       if ((ntiles + tps - 1) / tps != cand) continue;
       const double uneven = (double)(tps * cand) / (double)ntiles;
-      const int64_t w = base * cand, rounds = (w + slots - 1) / slots;
+      const int64_t w = base * cand;
+      const bool one_per_cu = upw == 1 && w <= (int64_t)c.n_cu;
+      const int64_t slots = (int64_t)c.n_cu * (upw == 1 && !one_per_cu ? 2 : 1);
+      const int64_t rounds = (w + slots - 1) / slots;
       double fill = (double)w / (double)(rounds * slots);
       if (cand == 1 && rounds >= 2 && window <= 0) {
         const double w_min = (double)(len_after - n_tokens) + kRowsPerUnit, w_mean = (double)len_after - 0.5 * n_tokens;
         fill = (double)w * w_mean / ((double)w * w_mean + (double)(rounds * slots - w) * w_min);
       }
-      const double rate = std::min(1.41 * fill, std::pow(fill, 0.3));
+      const double rate = std::min(1.41 * fill, std::pow(fill, 0.3)) * (one_per_cu ? 0.93 : 1.0);
       const double merge = cand > 1 ? (double)cand * rows * (f.head_dim + 2) * 8.0 / 4e12 + 6e-6 : 0.0;
       const double t = t_attn * uneven / rate * (1.0 + 0.03 / (double)rounds) + 8e-6 * (double)rounds + merge;
       if (t < best * 0.995) {
@@ -125,6 +135,7 @@ Plan plan_with(const PlanCtx& c, int n_tokens, int64_t len_after, int upw, int n
         s = cand;
       }
     }
+    pl.est_seconds = best;
   }
   if (s > s_max) s = s_max;
   pl.tiles_per_split = (int)((ntiles + s - 1) / s);
@@ -156,6 +167,9 @@ Plan choose_plan(const PlanCtx& c, int n_tokens, int64_t len_after, int n_sink, 
   const int64_t padded1 = (int64_t)p1.wgs_per_head * kUnitsPerWg, padded2 = (int64_t)p2.wgs_per_head * kUnitsPerWg * 2;
   if (padded2 * 5 > padded1 * 6) return p1;                                   // more than 20 % extra padding
   if ((int64_t)p2.n_wgs * 4 < (int64_t)c.n_cu * 3 && p1.n_wgs > p2.n_wgs) return p1;  // cannot fill the chip
+  // Some extra padding (odd group sizes: 28 units of a G = 7 head at C = 128 fill 3.5 two-unit workgroups): the
+  // time estimates of the two grids decide.
+  if (padded2 > padded1 && c.tune_splits == 0 && p1.est_seconds < p2.est_seconds) return p1;
   return p2;
 }
 

@@ -24,6 +24,7 @@ struct PlanCtx {
 
 struct Plan {
   int units_per_wave, units_per_head, wgs_per_head, n_splits, tiles_per_split, n_wgs, pair_order, pair_units;
+  double est_seconds;  // the planner's time estimate of the step (0 when the split count was forced)
 };
 
 int elem_size(int dtype);
