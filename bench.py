@@ -415,7 +415,7 @@ def main():
     roofline = {
         "kernel": "attn_bf16_kernel" if cfg.dtype == "bf16" else "attn_f32_kernel",
         "bound": "mfma", "achieved": r(attn_tflops), "peak": peak, "unit": "TFLOP/s", "frac": r(attn_tflops / peak, 4),
-        "traffic": None if tuning else measured_traffic(cfg.name),
+        "traffic": None if tuning or args.dtype or args.layers else measured_traffic(cfg.name + (f"_C{args.chunk}" if args.chunk else "")),
         "launches": n_prof, "avg_launch_ms": r(attn_avg_ms, 4), "flops_per_launch": round(w.flops / w.launches),
         "algorithmic_bytes_per_launch": round(w.bytes / w.launches),
     }
@@ -437,7 +437,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.n_layers} layers, Hq={cfg.n_q_heads}, Hkv={cfg.n_kv_heads}, d={cfg.head_dim}, "
                                f"C={cfg.chunk}, fold to {cfg.total_tokens} tokens = {w.launches} kvfold_step calls per bench "
-                               f"step ({w.flops / 1e15:.2f} PFLOP), {w.cache.bytes_required() / 2**30:.0f} GiB of K/V resident",
+                               f"step ({w.flops / 1e15:.3g} PFLOP), {w.cache.bytes_required() / 2**30:.3g} GiB of K/V resident",
                    "seed": I.BASE_SEED},
         "frac_of_bf16_peak": r(tflops / PEAK_BF16_TFLOPS, 4), "fold_tokens_per_s": round(tokens_per_s),
         "roofline": roofline,

@@ -63,6 +63,8 @@ def test_bytes_required_matches_paper_accounting(lib):
         need = kv.kvfold_cache_bytes_required(cfg)
         assert need == tokens * vals["bytes_per_token"]
         assert abs(need / 1e9 - gb) < 0.006          # the table prints two decimals
+    # the streaming baseline's configuration (Sec. 6): 4 sinks + 1020 recent tokens fill its 1024-token cache
+    assert vals["stream_sinks"] + vals["stream_window"] == vals["stream_capacity"] == 1024
     cfg.capacity_tokens = 131072
     assert kv.kvfold_cache_bytes_required(cfg) == 17179869184   # 16 GiB exactly
     # fp32 doubles it

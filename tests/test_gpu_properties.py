@@ -98,11 +98,13 @@ def test_determinism_and_stream_order(H):
     (8, 2, 128, [64, 128, 64, 192, 64], 3),          # split launches: pieces that end before the chunk begins
     (28, 4, 64, [128, 128, 16, 48, 64, 33, 31, 64], 0),   # lengths that leave and regain a multiple of 64
     (4, 4, 128, [512, 64, 1, 63, 512], 2),
+    (32, 8, 128, [1000, 1, 1, 16, 5, 1], 0),          # decode-shaped steps at lengths off the tile grid
+    (8, 2, 128, [777, 3, 100, 1, 64], 4),             # ... with the straddling tile inside a split piece
 ])
 def test_fused_append_equals_separate_append(H, Hq, Hkv, d, chunks, splits):
-    """bf16: when the cache length is a multiple of the 64-key tile the attention kernel copies the chunk's rows
-    into the cache itself and reads the chunk's tiles from k_new / v_new; switched off (tuning knob) the
-    separate append kernel runs first.  Same bits either way, outputs and cache."""
+    """bf16: the attention kernel copies the chunk's rows into the cache itself and reads the chunk's own rows from
+    k_new / v_new (a tile that straddles the cache's end is filled from both sides); switched off (tuning knob)
+    the separate append kernel runs first.  Same bits either way, outputs and cache."""
     cfg = I.FoldConfig("fused", 26, 1, Hq, Hkv, d, max(chunks), 0, "bf16")
     res = []
     for knob in (0, 1):
