@@ -352,7 +352,7 @@ def main():
     ap.add_argument("--dtype", default="", choices=["", "bf16", "f32"], help="override the workload's element type")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=160, help="sample rows of the oracle's timed leg")
+    ap.add_argument("--cpu-rows", type=int, default=400, help="sample rows of the oracle's timed leg")
     ap.add_argument("--detail", default="", help="write per-step curves of every workload to this JSON file")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--units-per-wave", type=int, default=0)
