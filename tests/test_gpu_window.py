@@ -160,3 +160,30 @@ def test_window_argument_errors(H):
         assert gpu.cache.length(0) == 64
     finally:
         gpu.close()
+
+
+def _random_window_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        d = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 3, 4]))
+        G = int(rng.choice([1, 2, 4, 7]))
+        n_chunks = int(rng.integers(2, 7))
+        chunks = [int(rng.choice([1, 5, 31, 32, 33, 64, 100, 128, 200, 256])) for _ in range(n_chunks)]
+        dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+        splits = int(rng.choice([0, 0, 2, 3]))
+        upw = int(rng.choice([0, 0, 1, 2]))
+        n_sink = int(rng.choice([0, 1, 4, 63, 64, 65, 130]))
+        window = int(rng.choice([1, 2, 17, 32, 63, 64, 65, 100, 129, 300, 1020]))
+        cases.append((dtype, Hkv * G, Hkv, d, tuple(chunks), n_sink, window, splits, upw))
+    return cases
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,chunks,n_sink,window,splits,upw", _random_window_cases(32, 20260513))
+def test_window_seeded_random_shapes(H, oracle, dtype, Hq, Hkv, d, chunks, n_sink, window, splits, upw):
+    """A seeded sweep over head counts, group sizes, head dims, ragged chunk sequences (cache lengths on and off the
+    tile grid), sink counts and window lengths around the tile and unit sizes, and launch shapes: every row and head of
+    every windowed step against the oracle, cache bit-exact."""
+    cfg = I.FoldConfig("window_rand", 56, 1, Hq, Hkv, d, max(chunks), 0, dtype)
+    _run_window_case(H, oracle, cfg, list(chunks), n_sink, window, splits=splits, upw=upw if dtype == "bf16" else 0)
