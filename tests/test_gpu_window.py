@@ -205,3 +205,61 @@ def test_window_with_logit_jumps(H, oracle, profile, dtype, upw, splits):
     peak = max(abs(I.LOGIT_PROFILES[profile](j)) for j in range(sum(chunks)))
     _run_window_case(H, oracle, cfg, chunks, 4, 150, splits=splits, upw=upw, profile=profile, check_lse=False,
                      tol=max(1e-5, 3e-6 * peak) if dtype == "f32" else None)
+
+
+def test_window_keeps_a_near_needle_and_loses_a_far_one(H, oracle):
+    """The paper's comparison at the operator level (Sec. 6: the streaming baseline retrieves only while the needle is
+    inside its window; the full cache retrieves at every distance).  Two needles are planted in a 10K-token fold at
+    C = 256, each a key row equal to 8 * sqrt(d) * q/|q| of its own probing (row, head) of the last chunk (logit about
+    90: the probe's weight sits on the needle, out = the needle's value row): one 300 tokens before its probe, one 8000
+    tokens before.  The plain step retrieves both; under 4 sinks + 1020 recent tokens the near one is retrieved and
+    the far one has weight exactly zero, so its probe's output is what the window alone gives."""
+    import math
+    cfg = I.FoldConfig("window_needles", 58, 1, 8, 2, 128, 256, 40 * 256, "bf16")
+    N, C, G = cfg.n_steps, cfg.chunk, 4
+    last = N - 1
+    q_last, _, _ = I.chunk_qkv(cfg, 0, last)
+    probes = {"near": (40, 1, 300), "far": (200, 6, 8000)}            # name: (row in the last chunk, query head, distance)
+    needles = {}
+    for name, (row, head, dist) in probes.items():
+        pos = last * C + row - dist
+        qv = q_last[row, head].float()
+        needles[name] = (pos, head // G, (8.0 * math.sqrt(cfg.head_dim) * qv / qv.norm()).to(torch.bfloat16))
+    plain, wind = H.GpuFold(cfg), H.GpuFold(cfg)
+    oc_p, oc_w = H.make_oracle(oracle, cfg), H.make_oracle(oracle, cfg)
+    rows = sorted(r for r, _, _ in probes.values())
+    try:
+        for step in range(N):
+            q, k, v = I.chunk_qkv(cfg, 0, step)
+            k = k.clone()
+            for pos, g, key in needles.values():
+                if pos // C == step:
+                    k[pos - step * C, g] = key
+            if step < last:
+                plain.step(0, q, k, v)
+                wind.step(0, q, k, v)
+                oc_p.append(H.bits(k), H.bits(v))
+                oc_w.append(H.bits(k), H.bits(v))
+            else:
+                out_p = plain.step(0, q, k, v)
+                out_w = wind.step(0, q, k, v, window=(4, 1020))
+                ref_p, _, w_p = H.oracle_step(oc_p, q, k, v, rows=rows, want_weights=True)
+                ref_w, _, w_w = H.oracle_step(oc_w, q, k, v, rows=rows, want_weights=True, window=(4, 1020))
+        torch.cuda.synchronize()
+        assert np.abs(H.wide(out_p)[rows] - ref_p).max() <= H.TOL["bf16"]
+        assert np.abs(H.wide(out_w)[rows] - ref_w).max() <= H.TOL["bf16"]
+        for name, (row, head, dist) in probes.items():
+            pos, g, _ = needles[name]
+            i = rows.index(row)
+            v_needle = oc_p.V[g, pos]                                  # the value row stored beside the needle key
+            assert int(w_p[i, head].argmax()) == pos and w_p[i, head, pos] > 0.99       # full cache: retrieved
+            assert np.abs(H.wide(out_p)[row, head] - v_needle).max() <= 3e-2
+            if name == "near":
+                assert int(w_w[i, head].argmax()) == pos and w_w[i, head, pos] > 0.99   # inside the window: retrieved
+                assert np.abs(H.wide(out_w)[row, head] - v_needle).max() <= 3e-2
+            else:
+                assert w_w[i, head, pos] == 0.0                                           # evicted: weight exactly zero
+                assert np.abs(H.wide(out_w)[row, head] - v_needle).max() > 0.5           # ... and the output shows it
+    finally:
+        plain.close()
+        wind.close()
