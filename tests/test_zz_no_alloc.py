@@ -98,3 +98,38 @@ def test_noalloc_rejects_steps_beyond_the_scratch_array():
         assert cache.length(0) == 2048
     finally:
         cache.close()
+
+
+def test_noalloc_step_under_graph_capture():
+    """The callers this entry point is for: a split step (64 pieces + merge, partials in the static array) captured into
+    a HIP graph and replayed several times, with eager work and synchronisations between the replays, gives the bits
+    of the eager call."""
+    cfg = I.FoldConfig("noalloc_graph", 63, 1, 8, 2, 128, 16, 0, "bf16")
+    C, L_prev = 16, 6000
+    cache = _filled_cache(cfg, 16, L_prev, 8192, 5)
+    try:
+        assert cache.plan(C, L_prev + C)[1] > 1
+        q, k, v = (t.to(DEV) for t in I.chunk_qkv(cfg, 0, 7, n_tokens=C, token_base=L_prev))
+        out = torch.empty_like(q)
+        lse = torch.empty((cfg.n_q_heads, C), dtype=torch.float32, device=DEV)
+        cache.step(0, q, k, v, out, lse=lse, noalloc=True)
+        torch.cuda.synchronize()
+        want, want_lse = out.clone(), lse.clone()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        cache.set_length(0, L_prev)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                cache.step(0, q, k, v, out, lse=lse, noalloc=True)
+        torch.cuda.synchronize()
+        scratch = torch.empty(1 << 20, device=DEV)
+        for _ in range(4):
+            out.zero_(); lse.zero_()
+            scratch.normal_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, want) and torch.equal(lse, want_lse)
+        assert cache.length(0) == L_prev + C
+    finally:
+        cache.close()
