@@ -63,6 +63,18 @@ def test_config2_llama_layer_16k(H, oracle):
     print("config 2 worst max-abs error", worst)
 
 
+def test_head_dim_64_at_benchmark_sizes(H, oracle):
+    """The d = 64 instantiations of the kernels at the sizes of configs 2 and 3 (the benchmark's own shapes all have
+    d = 128): C = 2048 to 16K, every step, sampled rows; C = 256 at cache lengths up to 64K in the split geometry,
+    sampled steps and rows; all heads."""
+    cfg = I.CONFIGS["llama_16k"].with_(name="llama_16k_d64", config_id=8, head_dim=64)
+    worst, _, _ = _run_sampled(H, oracle, cfg, [0], steps=list(range(cfg.n_steps)), rows_random=16)
+    cfg3 = I.CONFIGS["deep_chain_128k"].with_(name="deep_chain_64k_d64", config_id=9, head_dim=64, total_tokens=65536,
+                                              needle=False)
+    worst3, _, _ = _run_sampled(H, oracle, cfg3, [0], want_lse=True)
+    print("d = 64: worst max-abs errors", worst, worst3)
+
+
 def test_config3_deep_chain_needle_128k(H, oracle):
     """C=256, 512 chunks = 128K tokens, chain depth 511 (the paper's deepest operating point, Sec. 5),
     with a planted needle: a key row in chunk 0 equal to 8 * q/||q|| for a query row of the last chunk."""
