@@ -327,3 +327,31 @@ def test_plan_and_profile_api(H):
         assert n == 2 and a > 0 and t > 0 and m >= 0           # the append as its own kernel
     finally:
         gpu.close()
+
+
+def test_binding_rejects_mismatched_tensors_before_the_library_sees_them(H):
+    """The kernels trust element types and shapes, so the torch wrapper must stop a mismatch itself (a bf16 tensor
+    handed to an fp32 cache, a short k_new, a host tensor) with a ValueError; nothing is enqueued, the cache stays empty."""
+    cfg = I.FoldConfig("binding", 27, 1, 8, 2, 128, 64, 0, "f32")
+    gpu = H.GpuFold(cfg, capacity=128, chunk_tokens=64)
+    try:
+        q, k, v = (t.to(gpu.dev) for t in I.chunk_qkv(cfg, 0, 0))
+        out = torch.empty_like(q)
+        bad = [
+            (q.bfloat16(), k, v, out),                  # wrong element type
+            (q, k[:32], v, out),                        # short k_new
+            (q, k, v.cpu(), out),                       # host tensor
+            (q, k, v, out[:, :4]),                      # wrong head count (and not contiguous)
+            (q.transpose(0, 1), k, v, out),             # wrong layout
+        ]
+        for args in bad:
+            with pytest.raises(ValueError):
+                gpu.cache.step(0, *args)
+        with pytest.raises(ValueError):
+            gpu.cache.step(0, q, k, v, out, lse=torch.empty((8, 64), dtype=torch.float64, device=gpu.dev))
+        assert gpu.cache.length(0) == 0
+        gpu.cache.step(0, q, k, v, out)
+        torch.cuda.synchronize()
+        assert gpu.cache.length(0) == 64
+    finally:
+        gpu.close()
