@@ -263,3 +263,29 @@ def test_window_keeps_a_near_needle_and_loses_a_far_one(H, oracle):
     finally:
         plain.close()
         wind.close()
+
+
+@pytest.mark.parametrize("C,L_prev", [(2048, 14336), (4096, 4096), (1000, 9000)])
+def test_window_long_chunks_multi_round_grids(H, oracle, C, L_prev):
+    """Chunks far longer than the window (the windowed step of the 16K fold's last chunk, a 4096-row chunk, a ragged
+    one off the tile grid): many workgroups per KV head, each with its own first window tile and skip, grids of up to
+    two rounds; every row and head against the oracle."""
+    cfg = I.CONFIGS["llama_16k"].with_(name="window_long", config_id=10, chunk=C, total_tokens=L_prev + C)
+    gpu = H.GpuFold(cfg, capacity=L_prev + C, chunk_tokens=C)
+    oc = H.make_oracle(oracle, cfg, capacity=L_prev + C)
+    try:
+        kd, vd = gpu.cache.view(0)
+        _, k, v = I.chunk_qkv(cfg, 0, 0, n_tokens=L_prev, token_base=0)
+        oc.append(H.bits(k), H.bits(v))
+        kd[:, :L_prev].copy_(k.to(kd.device).transpose(0, 1))
+        vd[:, :L_prev].copy_(v.to(vd.device).transpose(0, 1))
+        gpu.cache.set_length(0, L_prev)
+        q, k, v = I.chunk_qkv(cfg, 0, 0, n_tokens=C, token_base=L_prev)
+        out, lse = gpu.step(0, q, k, v, want_lse=True, window=(4, 1020))
+        ref, ref_lse = H.oracle_step(oc, q, k, v, window=(4, 1020))
+        err = float(np.abs(H.wide(out) - ref).max())
+        assert err <= H.TOL["bf16"], f"max|out-oracle| = {err}"
+        assert np.abs(lse.cpu().double().numpy().T - ref_lse).max() <= 2e-2
+        H.assert_cache_bit_exact(gpu, oc)
+    finally:
+        gpu.close()
