@@ -22,6 +22,8 @@ HIPCC_FLAGS = [
     "-Rpass-analysis=kernel-resource-usage",
 ]
 RESOURCE_REPORT = os.path.join(LIB_DIR, "kernel_resources.txt")
+C_CLIENT_PATH = os.path.join(LIB_DIR, "kvfold_c_client")
+INCLUDE_DIR = os.path.join(os.path.dirname(_HERE), "include")
 
 
 def build_library(verbose: bool = False) -> str:
@@ -53,5 +55,18 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def build_c_client() -> str:
+    """Compile the plain-C caller of the library (gcc, C11, no HIP compiler): it sees only include/kvfold.h, the HIP
+    runtime API and the shared library."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O1", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__", "-I" + INCLUDE_DIR,
+           "-isystem", os.path.join(rocm, "include"), os.path.join(CSRC, "c_client.c"), "-o", C_CLIENT_PATH,
+           "-L" + LIB_DIR, "-lkvfold", "-L" + os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    subprocess.run(cmd, check=True)
+    return C_CLIENT_PATH
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_c_client())

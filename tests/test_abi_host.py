@@ -238,3 +238,15 @@ def test_kernels_use_no_scratch_memory():
         assert scratch == 0 and spill == 0, f"{name}: scratch {scratch} B/lane, {spill} spilled VGPRs"
         if "attn_bf16_kernelILi128ELi2" in name:   # the flagship kernel: one wave per SIMD, O (128) and Q (64) in AGPRs
             assert int(re.search(r"AGPRs: (\d+)", b).group(1)) >= 192
+
+
+def test_header_is_plain_c_and_the_c_client_builds(tmp_path):
+    """include/kvfold.h compiles as strict C99 on its own (no C++ or HIP in the interface), and the plain-C caller of the
+    library compiles with gcc and links against the built library."""
+    import subprocess
+    from paper_2605_12471_amd import build as B
+    src = tmp_path / "only_header.c"
+    src.write_text('#include "kvfold.h"\nint main(void) { kvfold_config_t c; c.struct_size = sizeof c; return (int)c.struct_size * 0; }\n')
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I" + B.INCLUDE_DIR, "-c", str(src),
+                    "-o", str(tmp_path / "only_header.o")], check=True)
+    assert os.path.exists(B.build_c_client())
