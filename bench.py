@@ -185,7 +185,7 @@ def cpu_baseline(w, torch, I, n_rows, layer=0):
     err = float(np.abs(w.out[rows].cpu().double().numpy() - ref).max())
     return {
         "value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": O.threads(), "kind": "oracle",
-        "sample": f"{len(rows)} seeded rows x {cfg.n_q_heads} heads of the last fold step of layer {layer} "
+        "sample": f"{len(rows)} seeded rows x {cfg.n_q_heads} heads of layer {layer}'s last step "
                   f"({L_prev + cfg.chunk} keys): {flops / 1e9:.0f} GFLOP fp64 in {dt:.1f} s",
         "gpu_max_abs_err_on_sample": round(err, 6),
     }
@@ -426,7 +426,7 @@ def main():
     pts = curve_points(cfg, w.per_step_curve(reps=2))
     detail["curve_" + cfg.name] = pts
     sel = pts if len(pts) <= 8 else pts[:: len(pts) // 4] + [pts[-1]]
-    curve = {"what": "single steps of layer 0 vs cache length before the step",
+    curve = {"what": "layer-0 steps vs length before the step",
              "L_prev": [p["L_prev"] for p in sel], "tflops": [round(p["tflops"]) for p in sel],
              "tokens_per_s": [round(p["tokens_per_s"]) for p in sel]}
 
@@ -453,6 +453,14 @@ def main():
 
     if not args.no_extra:
         extra = {}
+        # what this machine delivers right after the headline fold: a loop of nothing but bf16 matrix instructions, and a
+        # plain streaming read of 2 GiB (both in the library, kvfold_measure_peaks)
+        rc, box_tflops, box_gbps = kv.kvfold_measure_peaks(dev.index or 0)
+        if rc:
+            raise kv.KvFoldError(rc, "kvfold_measure_peaks")
+        extra["box_peaks"] = {"mfma_only_tflops": round(box_tflops), "hbm_read_GBps": round(box_gbps),
+                              "headline_vs_mfma_only": r(tflops / box_tflops, 3)}
+        detail["box_peaks"] = {"mfma_only_bf16_tflops": box_tflops, "hbm_read_GBps": box_gbps}
         # the other workloads of the benchmark definition, one layer each
         for name in ("llama_16k", "deep_chain_128k"):
             print("bench: extra", name, file=sys.stderr, flush=True)
@@ -469,19 +477,19 @@ def main():
             d = single_layer_fold("sweep_64k", torch, kv, I, dev, tuning, chunk=C, reps=2, curve=(C == 2048))
             detail[f"fold_sweep_64k_C{C}"] = d
             sweep[f"C{C}"] = [round(d["tflops"]), r(d["frac_of_bf16_peak"], 3)]
-        sweep["what"] = "[fold TFLOP/s, frac of bf16 peak]"
+        sweep["what"] = "[TFLOP/s, frac of peak]"
         extra["sweep_64k"] = sweep
         print("bench: extra decode", file=sys.stderr, flush=True)
         dec = decode_shaped_points(torch, kv, I, dev)
         detail["decode_shaped_128k"] = dec
         extra["decode_128k"] = {f"C{p['C']}": [round(p["roofline"]["achieved"]), r(p["roofline"]["frac"], 3),
                                                r(p["step_ms"] * 1e3, 1)] for p in dec}
-        extra["decode_128k"]["what"] = "[attention kernel GB/s, frac of 8 TB/s, whole step us]"
+        extra["decode_128k"]["what"] = "[attn GB/s, frac of 8 TB/s, step us]"
         print("bench: extra window", file=sys.stderr, flush=True)
         win = window_steps(torch, kv, I, dev)
         detail["window_4_1020_C256_128k"] = win
         extra["window_4+1020_C256_128k"] = {"step_us": r(win["step_us"], 1), "plain_step_us": r(win["plain_step_us"], 1),
-                                           "tflops": round(win["tflops"]), "algorithmic_GBps": round(win["algorithmic_GBps"])}
+                                           "tflops": round(win["tflops"]), "GBps": round(win["algorithmic_GBps"])}
         f32 = fp32_last_step(torch, kv, I, dev)
         detail["fp32_mode_sweep_64k_last_step"] = f32
         extra["fp32_C2048_L64k"] = {"tflops": r(f32["tflops"]), "frac_fp32_peak": r(f32["frac_of_fp32_mfma_peak"], 3)}

@@ -292,6 +292,21 @@ int kvfold_cache_profile_begin(kvfold_cache_t* cache, int32_t max_steps);
 int kvfold_cache_profile_end(kvfold_cache_t* cache, int32_t* n_steps /* host */, double* append_ms /* host */,
                              double* attention_ms /* host */, double* merge_ms /* host */);
 
+/*
+ * What this GPU delivers, for reports that quote an achieved rate beside the datasheet's (not part of the fold
+ * step): two stand-alone kernels, timed with HIP events on the default stream of `device`.
+ *   mfma_bf16_tflops  host or NULL: rate of a loop of nothing but 32x32x16 bf16 matrix instructions, one wavefront
+ *                     on every SIMD of every CU, operands in registers, no memory traffic -- the ceiling of any
+ *                     bf16 contraction on this part at the clock it sustains under that load.
+ *   hbm_read_gbps     host or NULL: rate of a plain streaming read (16 bytes per lane) of a 2 GiB buffer, far beyond
+ *                     every cache -- the ceiling of a read-bound step such as a decode-shaped one.
+ * Each figure is the mean of three timed passes after a warm-up pass (the matrix passes take about 50 ms each, so
+ * that the clock settles under the load).  Allocates (and frees) the 2 GiB buffer and a small output buffer,
+ * synchronises the device; takes about 0.25 s.  KVFOLD_ERR_INVALID_ARG for a bad device ordinal,
+ * KVFOLD_ERR_OOM / KVFOLD_ERR_HIP from the runtime.
+ */
+int kvfold_measure_peaks(int32_t device, double* mfma_bf16_tflops, double* hbm_read_gbps);
+
 /* Static, human-readable name of a status code. */
 const char* kvfold_status_string(int status);
 

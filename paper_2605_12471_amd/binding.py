@@ -106,6 +106,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvfold_cache_profile_end.restype = ctypes.c_int
     lib.kvfold_status_string.argtypes = [ctypes.c_int]
     lib.kvfold_status_string.restype = ctypes.c_char_p
+    lib.kvfold_measure_peaks.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.kvfold_measure_peaks.restype = ctypes.c_int
     lib.kvfold_last_hip_error.argtypes = []
     lib.kvfold_last_hip_error.restype = ctypes.c_int
     _lib = lib
@@ -219,6 +221,13 @@ def kvfold_cache_profile_end(cache):
 
 def kvfold_status_string(status: int) -> str:
     return load_library().kvfold_status_string(status).decode()
+
+
+def kvfold_measure_peaks(device=0, mfma=True, hbm=True):
+    """(status, bf16 matrix-instruction TFLOP/s or None, HBM read GB/s or None) of the GPU `device`."""
+    t, g = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    rc = load_library().kvfold_measure_peaks(device, ctypes.byref(t) if mfma else None, ctypes.byref(g) if hbm else None)
+    return rc, (t.value if mfma and rc == 0 else None), (g.value if hbm and rc == 0 else None)
 
 
 def kvfold_last_hip_error() -> int:

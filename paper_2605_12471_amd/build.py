@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_DIR = os.path.join(_HERE, "_lib")
 LIB_PATH = os.path.join(LIB_DIR, "libkvfold.so")
-SOURCES = ["kvfold_api.hip", "kvfold_plan.cpp", "append.hip", "attn_bf16.hip", "attn_f32.hip", "combine.hip"]
+SOURCES = ["kvfold_api.hip", "kvfold_plan.cpp", "append.hip", "attn_bf16.hip", "attn_f32.hip", "combine.hip", "peaks.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

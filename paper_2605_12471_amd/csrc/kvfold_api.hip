@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "../../include/kvfold.h"
+#include "kvfold_host.h"
 #include "kvfold_internal.h"
 
 using namespace kvfold;
@@ -37,14 +38,18 @@ struct kvfold_cache {
 };
 
 namespace {
-
 thread_local int g_last_hip_error = 0;
+}
 
+namespace kvfold {
 int hip_fail(hipError_t e) {
   g_last_hip_error = (int)e;
   (void)hipGetLastError();  // clear the sticky error
   return e == hipErrorOutOfMemory ? KVFOLD_ERR_OOM : KVFOLD_ERR_HIP;
 }
+}  // namespace kvfold
+
+namespace {
 
 // ---- static scratch of kvfold_step_noalloc: split partials for callers that cannot allocate ------------
 // One array per GPU, part of the library's code object, alive until the process ends.  Holds the (max, sum)
