@@ -126,11 +126,13 @@ def test_fused_append_equals_separate_append(H, Hq, Hkv, d, chunks, splits):
     assert torch.equal(res[0][1], res[1][1]) and torch.equal(res[0][2], res[1][2])
 
 
-@pytest.mark.parametrize("C,L_prev,dtype", [(256, 1024, "bf16"), (16, 4000, "bf16"), (64, 512, "f32")])
-def test_step_under_graph_capture(H, C, L_prev, dtype):
+@pytest.mark.parametrize("C,L_prev,dtype,mode", [(256, 1024, "bf16", "plain"), (16, 4000, "bf16", "plain"), (64, 512, "f32", "plain"),
+                                                 (256, 3000, "bf16", "window"), (16, 4000, "bf16", "rope"), (100, 1000, "f32", "window")])
+def test_step_under_graph_capture(H, C, L_prev, dtype, mode):
     """A step allocates nothing and only enqueues kernels, so it can be captured into a HIP graph: several
     replays, with eager work and synchronisations between them, give the bits of the eager step (unsplit and
-    split launches: append, attention, merge)."""
+    split launches: append, attention, merge; the plain step, the sink + sliding-window step and the step that
+    applies the rotary embedding itself)."""
     cfg = I.FoldConfig("graph", 25, 1, 8, 2, 128, C, 0, dtype)
     gpu = H.GpuFold(cfg, capacity=L_prev + C, chunk_tokens=max(C, 256))
     try:
@@ -143,7 +145,12 @@ def test_step_under_graph_capture(H, C, L_prev, dtype):
         q, k, v = (t.to(gpu.dev).contiguous() for t in I.chunk_qkv(cfg, 0, 99, n_tokens=C, token_base=L_prev))
         out = torch.empty_like(q)
         lse = torch.empty((cfg.n_q_heads, C), dtype=torch.float32, device=gpu.dev)
-        gpu.cache.step(0, q, k, v, out, lse=lse)
+        kw = {}
+        if mode == "window":
+            kw["window"] = (4, 300)
+        elif mode == "rope":
+            kw["rope"] = tuple(t.to(gpu.dev).contiguous() for t in I.rope_tables(cfg.head_dim, L_prev, C))
+        gpu.cache.step(0, q, k, v, out, lse=lse, **kw)
         torch.cuda.synchronize()
         want, want_lse = out.clone(), lse.clone()
         side = torch.cuda.Stream()
@@ -151,7 +158,7 @@ def test_step_under_graph_capture(H, C, L_prev, dtype):
         gpu.cache.set_length(0, L_prev)
         with torch.cuda.stream(side):
             with torch.cuda.graph(graph, stream=side):
-                gpu.cache.step(0, q, k, v, out, lse=lse)
+                gpu.cache.step(0, q, k, v, out, lse=lse, **kw)
         torch.cuda.synchronize()
         scratch = torch.empty(1 << 20, device=gpu.dev)
         for _ in range(4):
