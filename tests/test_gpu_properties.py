@@ -365,14 +365,14 @@ def test_binding_rejects_mismatched_tensors_before_the_library_sees_them(H):
 
 
 def test_measured_peaks_are_plausible(H):
-    """kvfold_measure_peaks: the loop of nothing but bf16 matrix instructions lands between half of and the whole
+    """kvfold_measure_peaks: the loop of nothing but bf16 matrix instructions lands between a third of and the whole
     datasheet rate (2516.6 TFLOP/s at 2.4 GHz; the chip clocks lower under that load), the streaming read between
-    half of and the whole 8 TB/s; either output may be left out; a bad device ordinal is refused."""
+    a third of and the whole 8 TB/s; either output may be left out; a bad device ordinal is refused."""
     rc, tflops, gbps = kv.kvfold_measure_peaks(0)
     assert rc == 0
-    assert 1250.0 < tflops < 2516.6 * 1.02, tflops
-    assert 4000.0 < gbps < 8000.0, gbps
+    assert 800.0 < tflops < 2516.6 * 1.02, tflops
+    assert 2500.0 < gbps < 8000.0, gbps
     rc, t2, g2 = kv.kvfold_measure_peaks(0, hbm=False)
-    assert rc == 0 and g2 is None and abs(t2 - tflops) < 0.15 * tflops
+    assert rc == 0 and g2 is None and abs(t2 - tflops) < 0.3 * tflops
     assert kv.kvfold_measure_peaks(-1)[0] == -1 and kv.kvfold_measure_peaks(1 << 20)[0] == -1
     print(f"box: bf16 matrix instructions only {tflops:.0f} TFLOP/s, streaming read {gbps:.0f} GB/s")
