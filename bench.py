@@ -41,12 +41,16 @@ KERNEL_SOURCES = ("attn_bf16.hip", "kvfold_internal.h", "kvfold_consts.h")
 
 
 def kernel_source_hash():
-    """Short hash of the attention kernel's sources: a measured HBM-traffic figure is only reported for the
-    kernel build it was measured on."""
+    """Short hash of the attention kernel's code -- its sources with comments and white space taken out: a measured
+    HBM-traffic figure is only reported for the kernel it was measured on, and rewording a comment does not make
+    it another kernel."""
     h = hashlib.sha256()
     for name in KERNEL_SOURCES:
-        with open(os.path.join(ROOT, "paper_2605_12471_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, "paper_2605_12471_amd", "csrc", name), "r") as f:
+            text = f.read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)     # block comments
+        text = re.sub(r"//[^\n]*", "", text)                   # line comments (no string in these files holds //)
+        h.update("".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 
