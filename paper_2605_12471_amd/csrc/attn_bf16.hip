@@ -4,9 +4,11 @@
 // rows j <= len_prev + i of KV head h / G -- the whole prefix plus the causal part of the chunk
 // itself:
 //     out[i][h] = sum_j softmax_j(scale * q[i][h] . K[j]) V[j].
-// The chunk's rows are either in the cache already (the append kernel ran first) or, when the cache
-// length is a multiple of the key tile, are read from k_new / v_new as handed in while this kernel
-// also copies them into the cache (fused append).
+// The chunk's rows are either in the cache already (the append kernel ran first) or are read from
+// k_new / v_new as handed in while this kernel also copies them into the cache (fused append; a key
+// tile with rows on both sides of the old cache's end is filled from both).  Under the sink +
+// sliding-window mask (Sec. 6, the streaming baseline) a row sees of those keys only the first
+// n_sink and the last `window`, and the key tiles in between are never touched.
 //
 // Mapping to the machine
 //  * Work unit = (32 consecutive chunk rows, one query head).  A wavefront owns QB units, a
