@@ -364,6 +364,8 @@ def main():
                     help="run only the decode-shaped points (1..16 tokens against a 128K cache) and print them: for profiling")
     ap.add_argument("--window-only", action="store_true",
                     help="run only the sink + sliding-window steps (4 + 1020 at C = 256 against 128K) and print them: for profiling")
+    ap.add_argument("--peaks-only", action="store_true",
+                    help="run only kvfold_measure_peaks (bf16 matrix instructions alone, streaming HBM read) and print it")
     ap.add_argument("--separate-append", action="store_true",
                     help="run the append as its own kernel (a plain copy of known size: the calibration of the HBM counters)")
     args = ap.parse_args()
@@ -382,6 +384,12 @@ def main():
     kv.load_library()  # fails loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.peaks_only:
+        rc, box_tflops, box_gbps = kv.kvfold_measure_peaks(0)
+        if rc:
+            raise kv.KvFoldError(rc, "kvfold_measure_peaks")
+        print(json.dumps({"box_peaks": {"mfma_only_bf16_tflops": box_tflops, "hbm_read_GBps": box_gbps}}))
+        return
     if args.decode_shaped_only:
         print(json.dumps({"decode_shaped_128k": decode_shaped_points(torch, kv, I, dev)}))
         return
